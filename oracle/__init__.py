@@ -1,0 +1,172 @@
+"""CPU oracle for the beam-search hot path.  TEST INFRASTRUCTURE ONLY.
+
+Only tests, the smoke check and the bench's cpu_baseline leg may import this
+package; the product (paper_2512_02278_amd) never does.  It wraps
+``beam_search.c`` (plain C, compiled with gcc) through ctypes and takes numpy
+arrays that live in host memory.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "beam_search.c")
+_LIB = os.path.join(_HERE, "liboracle.so")
+
+DT_U8, DT_F16, DT_F32 = 0, 1, 2
+L2, IP = 0, 1
+
+_NP_OF = {DT_U8: np.uint8, DT_F16: np.float16, DT_F32: np.float32}
+
+
+def build(force: bool = True) -> str:
+    """Compile beam_search.c into liboracle.so next to it (gcc, OpenMP over queries)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.run(
+            ["gcc", "-O2", "-std=c11", "-fopenmp", "-shared", "-fPIC", "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"],
+            check=True,
+        )
+    return _LIB
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build(force=False)
+        lib = ctypes.CDLL(_LIB)
+        lib.oracle_search.restype = ctypes.c_int
+        lib.oracle_bruteforce.restype = ctypes.c_int
+        lib.oracle_entries.restype = ctypes.c_int
+        lib.oracle_route.restype = ctypes.c_int
+        lib.oracle_threads.restype = ctypes.c_int
+        lib.oracle_keys.restype = None
+        _lib = lib
+    return _lib
+
+
+def dtype_code(arr: np.ndarray) -> int:
+    for code, t in _NP_OF.items():
+        if arr.dtype == t:
+            return code
+    raise TypeError(f"unsupported dtype {arr.dtype}")
+
+
+def _p(arr):
+    return None if arr is None else arr.ctypes.data_as(ctypes.c_void_p)
+
+
+def _c(arr, dtype=None):
+    if arr is None:
+        return None
+    a = np.ascontiguousarray(arr) if dtype is None else np.ascontiguousarray(arr, dtype=dtype)
+    return a
+
+
+class Index:
+    """Host-side description of one partition: vectors, graph, entry rule."""
+
+    def __init__(self, vectors, graph, metric=L2, n_entry=32, entry_mode=0, seed=0, centroids=None,
+                 cluster_offsets=None, route_c=0):
+        assert vectors.ndim == 2 and graph.ndim == 2 and graph.shape[0] == vectors.shape[0]
+        assert vectors.strides[1] == vectors.itemsize, "rows must be dense along dim"
+        self.vectors = vectors  # rows may be padded: the row stride is taken from .strides[0]
+        self.graph = _c(graph, np.int32)
+        self.metric, self.n_entry, self.entry_mode, self.seed = metric, n_entry, entry_mode, seed
+        self.dtype = dtype_code(vectors)
+        self.n, self.dim = vectors.shape
+        self.degree = graph.shape[1]
+        self.centroids = _c(centroids)
+        self.cluster_offsets = _c(cluster_offsets, np.int64)
+        self.n_clusters = 0 if centroids is None else centroids.shape[0]
+        self.route_c = route_c
+        if centroids is not None:
+            assert centroids.dtype == vectors.dtype and centroids.shape[1] == self.dim
+            assert self.cluster_offsets.shape[0] == self.n_clusters + 1
+
+    def _head(self):
+        return (_p(self.vectors), ctypes.c_int64(self.n), ctypes.c_int32(self.dim), ctypes.c_int32(self.dtype),
+                ctypes.c_int64(self.vectors.strides[0]), _p(self.graph), ctypes.c_int32(self.degree),
+                ctypes.c_int32(self.metric), ctypes.c_int32(self.n_entry), ctypes.c_int32(self.entry_mode),
+                ctypes.c_uint64(self.seed), _p(self.centroids), _p(self.cluster_offsets),
+                ctypes.c_int32(self.n_clusters), ctypes.c_int32(self.route_c))
+
+
+def search(index: Index, queries, k, itopk, width, max_iters, forget_visited=False, n_threads=0):
+    """Returns (ids[nq,k] int32, dists[nq,k] int32|float32, counters dict of int64[nq])."""
+    q = _c(queries)
+    assert q.dtype == index.vectors.dtype and q.ndim == 2 and q.shape[1] == index.dim
+    nq = q.shape[0]
+    ids = np.empty((nq, k), np.int32)
+    dists = np.empty((nq, k), np.int32 if index.dtype == DT_U8 else np.float32)
+    iters, ndist, npar = (np.zeros(nq, np.int64) for _ in range(3))
+    rc = _load().oracle_search(*index._head(), _p(q), ctypes.c_int64(nq), ctypes.c_int32(k), ctypes.c_int32(itopk),
+                               ctypes.c_int32(width), ctypes.c_int32(max_iters), ctypes.c_int32(int(forget_visited)),
+                               _p(ids), _p(dists), _p(iters), _p(ndist), _p(npar), ctypes.c_int32(n_threads))
+    if rc != 0:
+        raise ValueError("oracle_search rejected its arguments")
+    return ids, dists, {"iters": iters, "n_dist": ndist, "n_parents": npar}
+
+
+def bruteforce(vectors, queries, k, metric=L2):
+    """Exact top-k under (key, id) over all rows of `vectors`."""
+    q = _c(queries)
+    assert q.dtype == vectors.dtype and vectors.strides[1] == vectors.itemsize
+    nq = q.shape[0]
+    code = dtype_code(vectors)
+    ids = np.empty((nq, k), np.int32)
+    dists = np.empty((nq, k), np.int32 if code == DT_U8 else np.float32)
+    rc = _load().oracle_bruteforce(_p(vectors), ctypes.c_int64(vectors.shape[0]), ctypes.c_int32(vectors.shape[1]),
+                                   ctypes.c_int32(code), ctypes.c_int64(vectors.strides[0]), ctypes.c_int32(metric),
+                                   _p(q), ctypes.c_int64(nq), ctypes.c_int32(k), _p(ids), _p(dists))
+    if rc != 0:
+        raise ValueError("oracle_bruteforce rejected its arguments")
+    return ids, dists
+
+
+def keys(vectors, queries, ids, metric=L2):
+    """key(q_i, x_id) as float64 for ids[nq, r]; +inf where id < 0."""
+    q = _c(queries)
+    ids = _c(ids, np.int32)
+    out = np.empty(ids.shape, np.float64)
+    _load().oracle_keys(_p(vectors), ctypes.c_int32(vectors.shape[1]), ctypes.c_int32(dtype_code(vectors)),
+                        ctypes.c_int64(vectors.strides[0]), ctypes.c_int32(metric), _p(q),
+                        ctypes.c_int64(q.shape[0]), ctypes.c_int32(ids.shape[1]), _p(ids), _p(out))
+    return out
+
+
+def entries(index: Index, queries):
+    """Entry ids per query, [nq, n_entry] int32 (-1 where a slot produced none)."""
+    q = _c(queries)
+    out = np.empty((q.shape[0], index.n_entry), np.int32)
+    rc = _load().oracle_entries(ctypes.c_int64(index.n), ctypes.c_int32(index.dim), ctypes.c_int32(index.dtype),
+                                ctypes.c_int32(index.metric), ctypes.c_int32(index.n_entry),
+                                ctypes.c_int32(index.entry_mode), ctypes.c_uint64(index.seed), _p(index.centroids),
+                                _p(index.cluster_offsets), ctypes.c_int32(index.n_clusters),
+                                ctypes.c_int32(index.route_c), _p(q), ctypes.c_int64(q.shape[0]), _p(out))
+    if rc != 0:
+        raise ValueError("oracle_entries rejected its arguments")
+    return out
+
+
+def route(centroids, queries, route_c, metric=L2):
+    """The route_c nearest clusters per query under (key, cluster index)."""
+    q = _c(queries)
+    c = _c(centroids)
+    out = np.empty((q.shape[0], route_c), np.int32)
+    rc = _load().oracle_route(ctypes.c_int32(c.shape[1]), ctypes.c_int32(dtype_code(c)), ctypes.c_int32(metric),
+                              _p(c), ctypes.c_int32(c.shape[0]), ctypes.c_int32(route_c), _p(q),
+                              ctypes.c_int64(q.shape[0]), _p(out))
+    if rc != 0:
+        raise ValueError("oracle_route rejected its arguments")
+    return out
+
+
+def threads(n_threads=0) -> int:
+    return int(_load().oracle_threads(ctypes.c_int32(n_threads)))
