@@ -1,0 +1,133 @@
+/*
+ * libann: batched greedy beam search over a fixed-degree proximity graph, on the
+ * graph partition and vector partition one MI355X holds in HBM.
+ *
+ * This is the per-GPU "parallel vector search" step of Fantasy (Sec. 3.1, stage 3;
+ * cost model in Sec. 2 and Sec. 3.2 "Stage 3"): every query starts from entry
+ * nodes, repeatedly expands the best not-yet-expanded nodes of a fixed-size
+ * candidate list (beam width `width`, out-degree `degree`), scores their
+ * neighbours against the query and keeps the `itopk` best, and finally returns
+ * the first k.  The optional routed entry rule is the single-GPU form of stage 1
+ * ("K-means as classifier", Sec. 3.1): entries are drawn inside the clusters whose
+ * centroids are nearest to the query.
+ *
+ * Plain C ABI: pointers and sizes only.  Every pointer marked DEVICE must be
+ * memory of the current HIP device; everything else is host memory.  The library
+ * never takes ownership of caller memory.
+ *
+ * Order everywhere: ascending by (key, id) where
+ *     key = sum_j (q_j - x_j)^2      for ANN_L2
+ *     key = - sum_j q_j * x_j        for ANN_IP
+ * uint8 data gives exact int32 keys; fp16 / fp32 data accumulate in fp32.
+ */
+#ifndef ANN_H_
+#define ANN_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ann_index ann_index_t; /* opaque handle */
+
+enum { ANN_U8 = 0, ANN_F16 = 1, ANN_F32 = 2 };  /* element type of vectors, queries, centroids */
+enum { ANN_L2 = 0, ANN_IP = 1 };                /* metric */
+enum { ANN_ENTRY_UNIFORM = 0, ANN_ENTRY_ROUTED = 1 };
+enum {
+    ANN_OK = 0,
+    ANN_EINVAL = -1,       /* an argument is wrong (null pointer, size out of range, bad alignment) */
+    ANN_EUNSUPPORTED = -2, /* valid in principle, but no kernel variant is built for it */
+    ANN_ENOMEM = -3,       /* a host or device allocation failed */
+    ANN_EHIP = -4          /* a HIP runtime call failed; ann_last_error() has the text */
+};
+
+/*
+ * Description of one partition (Sec. 1 and Sec. 3.1: each GPU holds its share of the
+ * graph and of the vectors in HBM).  Copied by ann_index_load; the arrays it points
+ * to are borrowed and must stay alive and unchanged until ann_free.
+ */
+typedef struct {
+    const void* vectors;      /* DEVICE. n rows, row i at byte offset i*row_stride_bytes, 16-byte aligned */
+    int64_t n;                /* number of vectors, 1 .. 2^31-1 */
+    int32_t dim;              /* elements per vector; dim*sizeof(element) must be a multiple of 16 */
+    int32_t dtype;            /* ANN_U8 / ANN_F16 / ANN_F32 */
+    int64_t row_stride_bytes; /* >= dim*sizeof(element), multiple of 16 (128 keeps rows on cache lines) */
+    const int32_t* graph;     /* DEVICE. n*degree ids, row-major; a slot outside [0,n) is empty */
+    int32_t degree;           /* out-degree of the graph, >= 1 */
+    int32_t metric;           /* ANN_L2 / ANN_IP */
+    int32_t n_entry;          /* entry nodes drawn per query, >= 1 */
+    int32_t entry_mode;       /* ANN_ENTRY_UNIFORM or ANN_ENTRY_ROUTED */
+    uint64_t seed;            /* seed of the counter-based entry generator */
+    /* ANN_ENTRY_ROUTED only (ignored otherwise): */
+    const void* centroids;          /* DEVICE. n_clusters dense rows of `dim` elements, same dtype */
+    const int64_t* cluster_offsets; /* DEVICE. n_clusters+1 ascending ids; cluster c = [off[c], off[c+1]) */
+    int32_t n_clusters;             /* >= 1 */
+    int32_t route_c;                /* clusters a query is routed to, 1 .. min(n_clusters, 8) */
+} ann_index_desc_t;
+
+/*
+ * Entry rule.  Entry j (0 <= j < n_entry) of the query at position i of a call uses
+ *   z = splitmix64 output for state  seed + (i*n_entry + j + 1) * 0x9E3779B97F4A7C15
+ *   uniform:  e = z mod n
+ *   routed:   c = the (j mod route_c)-th nearest cluster of the query under
+ *             (key(query, centroid), cluster index);  e = off[c] + z mod |c|,
+ *             no entry if the cluster is empty.
+ * Duplicates count once.  Entries depend on the query's position in the call.
+ */
+
+/*
+ * Validates `desc`, chooses the kernel variant and returns a handle.
+ * No device memory is copied or allocated.  Must be called with the device that
+ * owns the arrays current.  Errors: ANN_EINVAL, ANN_EUNSUPPORTED, ANN_ENOMEM.
+ */
+int ann_index_load(const ann_index_desc_t* desc, ann_index_t** out_handle);
+
+/*
+ * Enqueues the search of `nq` queries on `stream` and returns without waiting.
+ *   queries    DEVICE, nq dense rows of `dim` elements of the index dtype, 16-byte aligned
+ *   k          results per query, 1 <= k <= itopk
+ *   itopk      size of the candidate list, 1 .. 512
+ *   width      nodes expanded per round (beam width w), width*degree <= 512
+ *   max_iters  upper bound on expansion rounds (the paper's I), >= 0; the search also
+ *              stops when every list entry has been expanded
+ *   out_ids    DEVICE, nq*k int32; -1 pads a query that reached fewer than k nodes
+ *   out_dists  DEVICE, nq*k keys: int32 for ANN_U8 (pad INT32_MAX), float otherwise (pad +inf)
+ *   stream     hipStream_t, NULL for the default stream
+ * Results are valid once the stream has been synchronised.  nq == 0 succeeds and
+ * launches nothing.  In routed mode a stream-ordered scratch of nq*route_c int32 is
+ * allocated and released on `stream`.  On error nothing is launched and the
+ * outputs are untouched.  Calls on different streams may share a handle.
+ */
+int ann_search(ann_index_t* handle, const void* queries, int64_t nq, int k, int itopk, int width, int max_iters,
+               int32_t* out_ids, void* out_dists, void* stream);
+
+/*
+ * Same as ann_search, and additionally writes four int32 per query to
+ * out_counters (DEVICE, nq*4, may be NULL): expansion rounds, keys computed
+ * (vector rows gathered), graph rows read, visited-table resets.
+ */
+int ann_search_counters(ann_index_t* handle, const void* queries, int64_t nq, int k, int itopk, int width,
+                        int max_iters, int32_t* out_ids, void* out_dists, int32_t* out_counters, void* stream);
+
+/*
+ * The routing step alone (routed indices only): for each query the route_c nearest
+ * clusters under (key(query, centroid), cluster index), ascending.
+ *   out_clusters  DEVICE, nq*route_c int32
+ */
+int ann_route(ann_index_t* handle, const void* queries, int64_t nq, int32_t* out_clusters, void* stream);
+
+/* Releases the handle (host memory only).  NULL is accepted. */
+int ann_free(ann_index_t* handle);
+
+/* Text of the calling thread's last error; never NULL. */
+const char* ann_last_error(void);
+
+/* Bytes of LDS one query's wavefront uses for the given search parameters, or a
+ * negative error code; lets callers reason about occupancy. */
+int64_t ann_lds_bytes(ann_index_t* handle, int itopk, int width);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ANN_H_ */

@@ -1,0 +1,256 @@
+// Host side of libann: argument checks, choice of kernel variant, launches.
+// Declarations and the meaning of every argument: include/ann.h.
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+
+#include "ann.h"
+#include "variants.h"
+
+namespace ann {
+
+// explicit specialisations live in the inst_*.hip files
+#define ANN_DECLARE(DT, METRIC, G, NCH)                                                                           \
+    template <>                                                                                                  \
+    hipError_t launch_search<DT, METRIC, G, NCH>(const SearchParams&, int, unsigned, size_t, hipStream_t);        \
+    template <>                                                                                                  \
+    hipError_t launch_route<DT, METRIC, G, NCH>(const RouteParams&, hipStream_t);
+ANN_ROW_VARIANTS(ANN_DECLARE)
+#undef ANN_DECLARE
+
+struct RowVariant {
+    int dtype, metric, g, nch;
+    hipError_t (*search)(const SearchParams&, int, unsigned, size_t, hipStream_t);
+    hipError_t (*route)(const RouteParams&, hipStream_t);
+};
+
+#define ANN_ENTRY(DT, METRIC, G, NCH) {DT, METRIC, G, NCH, &launch_search<DT, METRIC, G, NCH>, &launch_route<DT, METRIC, G, NCH>},
+static const RowVariant kRowVariants[] = {ANN_ROW_VARIANTS(ANN_ENTRY)};
+#undef ANN_ENTRY
+
+static thread_local char g_error[512] = "";
+
+static int fail(int code, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_error, sizeof(g_error), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+static int elem_size(int dtype) { return dtype == ANN_U8 ? 1 : dtype == ANN_F16 ? 2 : 4; }
+
+constexpr uint32_t kMagic = 0x414e4e31u;  // "ANN1"
+constexpr int kMaxItopk = 512, kMaxBatch = 512, kMaxWidth = 64;
+constexpr int64_t kMaxQueriesPerLaunch = 1 << 22;
+
+}  // namespace ann
+
+struct ann_index {
+    uint32_t magic;
+    ann_index_desc_t d;
+    int row_bytes;
+    const ann::RowVariant* variant;
+    int hash_bits_bias;  // ANN_HASH_BITS_BIAS: extra (or fewer) bits for the visited table, for tuning
+};
+
+using namespace ann;
+
+static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+extern "C" const char* ann_last_error(void) { return g_error; }
+
+extern "C" int ann_index_load(const ann_index_desc_t* desc, ann_index_t** out_handle) {
+    if (!desc || !out_handle) return fail(ANN_EINVAL, "ann_index_load: null argument");
+    *out_handle = nullptr;
+    const ann_index_desc_t& d = *desc;
+    if (!d.vectors || !d.graph) return fail(ANN_EINVAL, "ann_index_load: vectors and graph must not be null");
+    if (d.n < 1 || d.n > 2147483647ll) return fail(ANN_EINVAL, "ann_index_load: n = %lld outside 1..2^31-1", (long long)d.n);
+    if (d.dtype != ANN_U8 && d.dtype != ANN_F16 && d.dtype != ANN_F32)
+        return fail(ANN_EINVAL, "ann_index_load: unknown dtype %d", d.dtype);
+    if (d.metric != ANN_L2 && d.metric != ANN_IP) return fail(ANN_EINVAL, "ann_index_load: unknown metric %d", d.metric);
+    if (d.dim < 1) return fail(ANN_EINVAL, "ann_index_load: dim = %d", d.dim);
+    const int64_t row_bytes = (int64_t)d.dim * elem_size(d.dtype);
+    if (row_bytes % 16 != 0)
+        return fail(ANN_EINVAL, "ann_index_load: a row of %lld bytes is not a multiple of 16", (long long)row_bytes);
+    if (d.row_stride_bytes < row_bytes || d.row_stride_bytes % 16 != 0)
+        return fail(ANN_EINVAL, "ann_index_load: row_stride_bytes = %lld (rows are %lld bytes; must be a multiple of 16)",
+                    (long long)d.row_stride_bytes, (long long)row_bytes);
+    if (!aligned16(d.vectors)) return fail(ANN_EINVAL, "ann_index_load: vectors not 16-byte aligned");
+    if (d.degree < 1 || d.degree > kMaxBatch) return fail(ANN_EINVAL, "ann_index_load: degree = %d outside 1..%d", d.degree, kMaxBatch);
+    if (d.n_entry < 1 || d.n_entry > kMaxBatch)
+        return fail(ANN_EINVAL, "ann_index_load: n_entry = %d outside 1..%d", d.n_entry, kMaxBatch);
+    if (d.entry_mode != ANN_ENTRY_UNIFORM && d.entry_mode != ANN_ENTRY_ROUTED)
+        return fail(ANN_EINVAL, "ann_index_load: unknown entry_mode %d", d.entry_mode);
+    if (d.entry_mode == ANN_ENTRY_ROUTED) {
+        if (!d.centroids || !d.cluster_offsets) return fail(ANN_EINVAL, "ann_index_load: routed entries need centroids and cluster_offsets");
+        if (!aligned16(d.centroids)) return fail(ANN_EINVAL, "ann_index_load: centroids not 16-byte aligned");
+        if (d.n_clusters < 1) return fail(ANN_EINVAL, "ann_index_load: n_clusters = %d", d.n_clusters);
+        if (d.route_c < 1 || d.route_c > d.n_clusters || d.route_c > kMaxRouteC)
+            return fail(ANN_EINVAL, "ann_index_load: route_c = %d outside 1..min(n_clusters, %d)", d.route_c, kMaxRouteC);
+    }
+    const RowVariant* best = nullptr;
+    for (const RowVariant& v : kRowVariants)
+        if (v.dtype == d.dtype && v.metric == d.metric && (int64_t)v.g * v.nch * 16 >= row_bytes &&
+            (!best || v.g * v.nch < best->g * best->nch))
+            best = &v;
+    if (!best) return fail(ANN_EUNSUPPORTED, "ann_index_load: no kernel variant for rows of %lld bytes of this dtype", (long long)row_bytes);
+    ann_index* h = new (std::nothrow) ann_index;
+    if (!h) return fail(ANN_ENOMEM, "ann_index_load: out of host memory");
+    h->magic = kMagic;
+    h->d = d;
+    h->row_bytes = (int)row_bytes;
+    h->variant = best;
+    const char* bias = getenv("ANN_HASH_BITS_BIAS");
+    h->hash_bits_bias = bias ? atoi(bias) : 0;
+    *out_handle = h;
+    return ANN_OK;
+}
+
+extern "C" int ann_free(ann_index_t* h) {
+    if (!h) return ANN_OK;
+    if (h->magic != kMagic) return fail(ANN_EINVAL, "ann_free: not a live handle");
+    h->magic = 0;
+    delete h;
+    return ANN_OK;
+}
+
+namespace {
+
+struct Plan {
+    int list_variant, cap, hash_bits;
+    size_t lds_bytes;
+};
+
+int make_plan(const ann_index* h, int itopk, int width, Plan* plan, const char* who) {
+    if (itopk < 1 || itopk > kMaxItopk) return fail(ANN_EUNSUPPORTED, "%s: itopk = %d outside 1..%d", who, itopk, kMaxItopk);
+    if (width < 1 || width > kMaxWidth) return fail(ANN_EUNSUPPORTED, "%s: width = %d outside 1..%d", who, width, kMaxWidth);
+    const int64_t batch = (int64_t)width * h->d.degree;
+    if (batch > kMaxBatch) return fail(ANN_EUNSUPPORTED, "%s: width*degree = %lld above %d", who, (long long)batch, kMaxBatch);
+    const int need = (int)(batch > h->d.n_entry ? batch : h->d.n_entry);
+    int lv = -1;
+    for (int i = 0; i < kNumListVariants; ++i)
+        if (64 * kListVariants[i][0] >= itopk && 64 * kListVariants[i][1] >= need) {
+            lv = i;
+            break;
+        }
+    if (lv < 0) return fail(ANN_EUNSUPPORTED, "%s: no list variant for itopk = %d, batch = %d", who, itopk, need);
+    plan->list_variant = lv;
+    plan->cap = 64 * kListVariants[lv][1];
+    // the table is emptied once 3/4 full; right after that it holds <= itopk ids and one
+    // round adds <= need, so 3/4 of its size must cover itopk + need
+    int bits = 6;
+    while (((3 << bits) >> 2) < itopk + need) ++bits;
+    bits += 1 + h->hash_bits_bias;  // default: one more bit, so that resets are rare
+    while (((3 << bits) >> 2) < itopk + need) ++bits;
+    if (bits > 13) bits = 13;
+    plan->hash_bits = bits;
+    plan->lds_bytes = sizeof(uint32_t) * ((size_t(1) << bits) + 3 * (size_t)plan->cap + 64);
+    return ANN_OK;
+}
+
+}  // namespace
+
+extern "C" int64_t ann_lds_bytes(ann_index_t* h, int itopk, int width) {
+    if (!h || h->magic != kMagic) return fail(ANN_EINVAL, "ann_lds_bytes: not a live handle");
+    Plan plan;
+    const int rc = make_plan(h, itopk, width, &plan, "ann_lds_bytes");
+    return rc != ANN_OK ? rc : (int64_t)plan.lds_bytes;
+}
+
+extern "C" int ann_route(ann_index_t* h, const void* queries, int64_t nq, int32_t* out_clusters, void* stream) {
+    if (!h || h->magic != kMagic) return fail(ANN_EINVAL, "ann_route: not a live handle");
+    if (h->d.entry_mode != ANN_ENTRY_ROUTED) return fail(ANN_EINVAL, "ann_route: the index has no centroids");
+    if (nq < 0) return fail(ANN_EINVAL, "ann_route: nq = %lld", (long long)nq);
+    if (nq == 0) return ANN_OK;
+    if (!queries || !out_clusters) return fail(ANN_EINVAL, "ann_route: null argument");
+    if (!aligned16(queries)) return fail(ANN_EINVAL, "ann_route: queries not 16-byte aligned");
+    for (int64_t q0 = 0; q0 < nq; q0 += kMaxQueriesPerLaunch) {
+        RouteParams rp;
+        rp.centroids = static_cast<const uint8_t*>(h->d.centroids);
+        rp.n_clusters = h->d.n_clusters;
+        rp.row_bytes = h->row_bytes;
+        rp.queries = static_cast<const uint8_t*>(queries) + q0 * h->row_bytes;
+        rp.nq = nq - q0 < kMaxQueriesPerLaunch ? nq - q0 : kMaxQueriesPerLaunch;
+        rp.route_c = h->d.route_c;
+        rp.out = out_clusters + q0 * h->d.route_c;
+        const hipError_t e = h->variant->route(rp, static_cast<hipStream_t>(stream));
+        if (e != hipSuccess) return fail(ANN_EHIP, "ann_route: launch failed: %s", hipGetErrorString(e));
+    }
+    return ANN_OK;
+}
+
+extern "C" int ann_search_counters(ann_index_t* h, const void* queries, int64_t nq, int k, int itopk, int width,
+                                   int max_iters, int32_t* out_ids, void* out_dists, int32_t* out_counters,
+                                   void* stream_) {
+    if (!h || h->magic != kMagic) return fail(ANN_EINVAL, "ann_search: not a live handle");
+    if (nq < 0) return fail(ANN_EINVAL, "ann_search: nq = %lld", (long long)nq);
+    if (k < 1 || k > itopk) return fail(ANN_EINVAL, "ann_search: k = %d outside 1..itopk (%d)", k, itopk);
+    if (max_iters < 0) return fail(ANN_EINVAL, "ann_search: max_iters = %d", max_iters);
+    Plan plan;
+    const int rc = make_plan(h, itopk, width, &plan, "ann_search");
+    if (rc != ANN_OK) return rc;
+    if (nq == 0) return ANN_OK;
+    if (!queries || !out_ids || !out_dists) return fail(ANN_EINVAL, "ann_search: null argument");
+    if (!aligned16(queries)) return fail(ANN_EINVAL, "ann_search: queries not 16-byte aligned");
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+
+    int32_t* route = nullptr;
+    if (h->d.entry_mode == ANN_ENTRY_ROUTED) {
+        const hipError_t e = hipMallocAsync(reinterpret_cast<void**>(&route), sizeof(int32_t) * (size_t)nq * h->d.route_c, stream);
+        if (e != hipSuccess) return fail(ANN_ENOMEM, "ann_search: scratch allocation failed: %s", hipGetErrorString(e));
+        const int r = ann_route(h, queries, nq, route, stream);
+        if (r != ANN_OK) {
+            (void)hipFreeAsync(route, stream);
+            return r;
+        }
+    }
+
+    int result = ANN_OK;
+    for (int64_t q0 = 0; q0 < nq; q0 += kMaxQueriesPerLaunch) {
+        const int64_t cnt = nq - q0 < kMaxQueriesPerLaunch ? nq - q0 : kMaxQueriesPerLaunch;
+        SearchParams p;
+        p.vectors = static_cast<const uint8_t*>(h->d.vectors);
+        p.n = h->d.n;
+        p.row_stride = h->d.row_stride_bytes;
+        p.row_bytes = h->row_bytes;
+        p.graph = h->d.graph;
+        p.degree = h->d.degree;
+        p.queries = static_cast<const uint8_t*>(queries);
+        p.nq = nq;
+        p.q_base = q0;
+        p.q_count = cnt;
+        p.q_per_xcd = (cnt + 7) / 8;
+        p.k = k;
+        p.itopk = itopk;
+        p.width = width;
+        p.max_iters = max_iters;
+        p.n_entry = h->d.n_entry;
+        p.entry_mode = h->d.entry_mode;
+        p.seed = h->d.seed;
+        p.route = route;
+        p.cluster_offsets = h->d.cluster_offsets;
+        p.route_c = h->d.route_c;
+        p.hash_bits = plan.hash_bits;
+        p.cap = plan.cap;
+        p.out_ids = out_ids;
+        p.out_dists = static_cast<uint32_t*>(out_dists);
+        p.out_counters = out_counters;
+        const hipError_t e = h->variant->search(p, plan.list_variant, (unsigned)(8 * p.q_per_xcd), plan.lds_bytes, stream);
+        if (e != hipSuccess) {
+            result = fail(ANN_EHIP, "ann_search: launch failed: %s", hipGetErrorString(e));
+            break;
+        }
+    }
+    if (route) (void)hipFreeAsync(route, stream);
+    return result;
+}
+
+extern "C" int ann_search(ann_index_t* h, const void* queries, int64_t nq, int k, int itopk, int width, int max_iters,
+                          int32_t* out_ids, void* out_dists, void* stream) {
+    return ann_search_counters(h, queries, nq, k, itopk, width, max_iters, out_ids, out_dists, nullptr, stream);
+}

@@ -1,0 +1,303 @@
+// Beam search kernel: one wavefront (64 lanes) per query.
+//
+// State of a query:
+//   * candidate list: 64*LPL packed keys in registers, ascending, blocked layout
+//     (wave.h).  A packed key is (ordered key << 32) | (id << 1) | expanded, so one
+//     unsigned 64-bit compare orders by (key, id) and the expanded mark rides along.
+//   * visited table: open-addressing hash of ids in LDS.  It is emptied when it
+//     fills up and the ids of the current list are put back.  Forgetting other
+//     nodes cannot change the result: the list always holds the itopk best of all
+//     nodes scored so far and its worst key never rises, so a forgotten node that
+//     is scored again is rejected again; list members are always in the table and
+//     are never scored twice.  Only the number of rows gathered grows.
+//   * per round: parent ids, surviving neighbour ids and their packed keys in LDS.
+//
+// One round (Fantasy Sec. 3.2, stage 3: beam width w, out-degree d_g):
+//   pick <= width unexpanded list heads -> read their graph rows -> drop ids that
+//   are invalid or in the visited table -> gather the surviving rows (G lanes per
+//   row, contiguous 16-byte pieces) and compute keys -> sort the new keys (bitonic,
+//   in registers) -> merge with the list, keep the itopk smallest.
+#pragma once
+
+#include "row_ops.h"
+
+namespace ann {
+
+struct SearchParams {
+    const uint8_t* vectors;
+    int64_t n;
+    int64_t row_stride;
+    int32_t row_bytes;
+    const int32_t* graph;
+    int32_t degree;
+    const uint8_t* queries;
+    int64_t nq;
+    int64_t q_base, q_count;  // this launch serves queries [q_base, q_base + q_count)
+    int32_t k, itopk, width, max_iters;
+    int32_t n_entry, entry_mode;
+    uint64_t seed;
+    const int32_t* route;            // nq * route_c nearest clusters (routed mode)
+    const int64_t* cluster_offsets;  // routed mode
+    int32_t route_c;
+    int32_t hash_bits;  // visited table has 1 << hash_bits slots
+    int32_t cap;        // most candidates one round can produce, multiple of 64
+    int32_t* out_ids;
+    uint32_t* out_dists;
+    int32_t* out_counters;  // nq * 4 or null
+    int64_t q_per_xcd;      // queries of this launch handed to each of the 8 XCDs
+};
+
+constexpr uint32_t kEmptySlot = 0xffffffffu;
+
+__device__ __forceinline__ uint64_t splitmix64_at(uint64_t seed, uint64_t counter) {
+    uint64_t z = seed + (counter + 1) * 0x9E3779B97F4A7C15ull;
+    z ^= z >> 30;
+    z *= 0xBF58476D1CE4E5B9ull;
+    z ^= z >> 27;
+    z *= 0x94D049BB133111EBull;
+    z ^= z >> 31;
+    return z;
+}
+
+// True if `id` was not in the table (and now is).  The table is never full.
+__device__ __forceinline__ bool visited_insert(uint32_t* table, int hash_bits, uint32_t id) {
+    const uint32_t mask = (1u << hash_bits) - 1u;
+    uint32_t h = (id * 0x9E3779B1u) >> (32 - hash_bits);
+    for (;;) {
+        const uint32_t old = atomicCAS(&table[h], kEmptySlot, id);
+        if (old == kEmptySlot) return true;
+        if (old == id) return false;
+        h = (h + 1) & mask;
+    }
+}
+
+__device__ __forceinline__ void lds_sync() { __syncthreads(); }  // one wavefront per workgroup
+
+template <class Row, int LPL, int CPL>
+struct BeamSearch {
+    static constexpr int G = Row::G;
+    static constexpr int NCH = Row::NCH;
+    static constexpr int RPS = 64 / G;                                // rows per gather step
+    static constexpr int U = NCH >= 4 ? 1 : (NCH >= 2 ? 2 : 4);       // gather steps in flight
+    static constexpr int BR = LPL >= 2 ? 2 : 1;                       // registers of a sort batch
+
+    const SearchParams& p;
+    int lane;
+    uint32_t* table;
+    uint64_t* ckey;
+    uint32_t* cid;
+    uint32_t* parents;
+    Row row;
+    uint64_t L[LPL];
+    int n_table;  // ids in the visited table
+    int n_dist, n_parents, n_resets;
+
+    __device__ __forceinline__ BeamSearch(const SearchParams& p_, uint32_t* lds, int lane_) : p(p_), lane(lane_) {
+        table = lds;
+        ckey = reinterpret_cast<uint64_t*>(lds + (1 << p.hash_bits));
+        cid = lds + (1 << p.hash_bits) + 2 * p.cap;
+        parents = cid + p.cap;
+        n_table = n_dist = n_parents = n_resets = 0;
+    }
+
+    __device__ __forceinline__ void clear_table() {
+        for (int i = lane; i < (1 << p.hash_bits); i += 64) table[i] = kEmptySlot;
+        n_table = 0;
+    }
+
+    // Empties the table and puts the list's ids back.
+    __device__ __forceinline__ void reset_table() {
+        clear_table();
+        lds_sync();
+#pragma unroll
+        for (int r = 0; r < LPL; ++r) {
+            const bool have = L[r] != kInfKey;
+            if (have) visited_insert(table, p.hash_bits, (uint32_t)L[r] >> 1);
+            n_table += __builtin_popcountll(__ballot(have));
+        }
+        ++n_resets;
+    }
+
+    // Candidate ids held one per lane and round t: keep the unseen ones, packed into cid[0..m).
+    __device__ __forceinline__ void filter_into(int32_t id, bool valid, int& m) {
+        const bool ok = valid && id >= 0 && (int64_t)id < p.n && visited_insert(table, p.hash_bits, (uint32_t)id);
+        const uint64_t b = __ballot(ok);
+        if (ok) cid[m + rank_below(b)] = (uint32_t)id;
+        m += __builtin_popcountll(b);
+    }
+
+    // Gathers rows cid[0..m) and writes their packed keys to ckey[0..m).
+    __device__ __forceinline__ void score(int m) {
+        const int grp = lane / G;
+        for (int j0 = 0; j0 < m; j0 += RPS * U) {
+            u32x4 x[U][NCH];
+            uint32_t id[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int j = j0 + u * RPS + grp;
+                const bool live = j < m;
+                id[u] = live ? cid[j] : 0u;
+                row.load_row(x[u], p.vectors + (int64_t)id[u] * p.row_stride, live);
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int j = j0 + u * RPS + grp;
+                const uint32_t okey = row.key(x[u], lane);
+                if (j < m && row.lg == 0) ckey[j] = ((uint64_t)okey << 32) | ((uint64_t)id[u] << 1);
+            }
+        }
+        n_dist += m;
+    }
+
+    // list <- itopk smallest of list U ckey[base .. base + 64*R), R registers per lane.
+    template <int R>
+    __device__ __forceinline__ void merge_batch(int base, int m) {
+        uint64_t c[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const int j = base + lane * R + r;
+            c[r] = j < m ? ckey[j] : kInfKey;
+        }
+        bitonic_sort<R>(c, lane);
+        lds_sync();  // all reads of this batch done before it is overwritten
+#pragma unroll
+        for (int r = 0; r < R; ++r) ckey[base + lane * R + r] = c[r];
+        lds_sync();
+        // smallest 64*LPL of (list, sorted batch): element e against batch element 64*LPL-1-e
+#pragma unroll
+        for (int r = 0; r < LPL; ++r) {
+            const int j = 64 * LPL - 1 - (lane * LPL + r);
+            const uint64_t o = j < 64 * R ? ckey[base + j] : kInfKey;
+            L[r] = o < L[r] ? o : L[r];
+        }
+        bitonic_merge<LPL>(L, lane);
+#pragma unroll
+        for (int r = 0; r < LPL; ++r)
+            if (lane * LPL + r >= p.itopk) L[r] = kInfKey;
+        lds_sync();
+    }
+
+    __device__ __forceinline__ void merge_all(int m) {
+        int base = 0;
+        if constexpr (BR == 2) {
+            for (; m - base > 64; base += 128) merge_batch<2>(base, m);
+        }
+        for (; base < m; base += 64) merge_batch<1>(base, m);
+    }
+
+    __device__ __forceinline__ void run(int64_t qi) {
+        row.load_query(p.queries + qi * (int64_t)p.row_bytes, p.row_bytes, lane);
+#pragma unroll
+        for (int r = 0; r < LPL; ++r) L[r] = kInfKey;
+        clear_table();
+        lds_sync();
+
+        // entries (duplicates collapse in the visited table)
+        int m = 0;
+#pragma unroll
+        for (int t = 0; t < CPL; ++t) {
+            const int j = t * 64 + lane;
+            const bool valid = j < p.n_entry;
+            int32_t e = -1;
+            if (valid) {
+                const uint64_t z = splitmix64_at(p.seed, (uint64_t)qi * (uint64_t)p.n_entry + (uint64_t)j);
+                if (p.entry_mode == 0) {
+                    e = (int32_t)(z % (uint64_t)p.n);
+                } else {
+                    const int32_t c = p.route[qi * p.route_c + (j % p.route_c)];
+                    const int64_t lo = p.cluster_offsets[c], hi = p.cluster_offsets[c + 1];
+                    if (hi > lo) e = (int32_t)(lo + (int64_t)(z % (uint64_t)(hi - lo)));
+                }
+            }
+            filter_into(e, valid, m);
+        }
+        n_table += m;
+        lds_sync();
+        score(m);
+        lds_sync();
+        merge_all(m);
+
+        const int limit = (3 << p.hash_bits) >> 2;
+        int iters = 0;
+        for (; iters < p.max_iters; ++iters) {
+            // parents: the first <= width unexpanded entries in list order
+            int before = 0, total = 0;
+            bool un[LPL];
+#pragma unroll
+            for (int r = 0; r < LPL; ++r) {
+                un[r] = (L[r] & 1ull) == 0;
+                const uint64_t b = __ballot(un[r]);
+                before += rank_below(b);
+                total += __builtin_popcountll(b);
+            }
+            if (total == 0) break;
+            const int np = total < p.width ? total : p.width;
+#pragma unroll
+            for (int r = 0; r < LPL; ++r) {
+                if (un[r]) {
+                    if (before < np) {
+                        parents[before] = (uint32_t)L[r] >> 1;
+                        L[r] |= 1ull;
+                    }
+                    ++before;
+                }
+            }
+            n_parents += np;
+            if (n_table + np * p.degree > limit) reset_table();
+            lds_sync();
+
+            // neighbour ids of the parents, 64 per step, all loads issued first
+            const int nref = np * p.degree;
+            int32_t nb[CPL];
+#pragma unroll
+            for (int t = 0; t < CPL; ++t) {
+                const int s = t * 64 + lane;
+                nb[t] = -1;
+                if (s < nref) {
+                    const int pi = s / p.degree;
+                    nb[t] = __builtin_nontemporal_load(p.graph + (int64_t)parents[pi] * p.degree + (s - pi * p.degree));
+                }
+            }
+            m = 0;
+#pragma unroll
+            for (int t = 0; t < CPL; ++t) filter_into(nb[t], t * 64 + lane < nref, m);
+            n_table += m;
+            lds_sync();
+            score(m);
+            lds_sync();
+            merge_all(m);
+        }
+
+        // first k list entries
+#pragma unroll
+        for (int r = 0; r < LPL; ++r) {
+            const int e = lane * LPL + r;
+            if (e < p.k) {
+                const bool have = L[r] != kInfKey;
+                p.out_ids[qi * p.k + e] = have ? (int32_t)((uint32_t)L[r] >> 1) : -1;
+                p.out_dists[qi * p.k + e] = have ? Row::key_to_output((uint32_t)(L[r] >> 32)) : Row::pad_output();
+            }
+        }
+        if (p.out_counters && lane == 0) {
+            int32_t* c = p.out_counters + qi * 4;
+            c[0] = iters;
+            c[1] = n_dist;
+            c[2] = n_parents;
+            c[3] = n_resets;
+        }
+    }
+};
+
+// Workgroup b runs on XCD b % 8 (round-robin dispatch), so consecutive queries are
+// kept on one XCD and its L2: query = (b % 8) * q_per_xcd + b / 8.
+template <class Row, int LPL, int CPL>
+__global__ void __launch_bounds__(64) beam_search_kernel(const SearchParams p) {
+    extern __shared__ uint32_t lds[];
+    const int64_t b = blockIdx.x;
+    const int64_t local = (b & 7) * p.q_per_xcd + (b >> 3);
+    if (local >= p.q_count) return;
+    BeamSearch<Row, LPL, CPL> s(p, lds, lane_id());
+    s.run(p.q_base + local);
+}
+
+}  // namespace ann

@@ -1,0 +1,111 @@
+"""The C-ABI library without a GPU: it loads, exports what include/ann.h declares, and
+turns every bad argument into an error code (no launch is attempted on these paths)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2512_02278_amd import ann
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x7F0000000000  # a non-null, 16-byte aligned address that is never dereferenced on these paths
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "ann.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ann_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = ann.lib()
+    names = declared_functions()
+    assert set(names) == set(ann.EXPORTS)
+    for name in names:
+        assert getattr(L, name) is not None
+
+
+def desc(**kw):
+    d = ann.ann_index_desc_t()
+    d.vectors, d.n, d.dim, d.dtype, d.row_stride_bytes = FAKE, 1000, 128, ann.ANN_U8, 128
+    d.graph, d.degree, d.metric, d.n_entry, d.entry_mode, d.seed = FAKE, 32, ann.ANN_L2, 32, 0, 1
+    for k, v in kw.items():
+        setattr(d, k, v)
+    return d
+
+
+def load(d):
+    h = ctypes.c_void_p()
+    rc = ann.lib().ann_index_load(ctypes.byref(d), ctypes.byref(h))
+    return rc, h
+
+
+def test_load_and_free_roundtrip():
+    rc, h = load(desc())
+    assert rc == ann.ANN_OK and h.value
+    assert ann.lib().ann_lds_bytes(h, 128, 4) > 0
+    assert ann.lib().ann_free(h) == ann.ANN_OK
+    assert ann.lib().ann_free(None) == ann.ANN_OK
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(vectors=None), ann.ANN_EINVAL),
+    (dict(graph=None), ann.ANN_EINVAL),
+    (dict(n=0), ann.ANN_EINVAL),
+    (dict(n=2**31), ann.ANN_EINVAL),
+    (dict(dtype=7), ann.ANN_EINVAL),
+    (dict(metric=5), ann.ANN_EINVAL),
+    (dict(dim=100, row_stride_bytes=112), ann.ANN_EINVAL),      # 100 bytes: not a multiple of 16
+    (dict(row_stride_bytes=64), ann.ANN_EINVAL),                # stride below the row length
+    (dict(row_stride_bytes=136), ann.ANN_EINVAL),               # stride not a multiple of 16
+    (dict(vectors=FAKE + 8), ann.ANN_EINVAL),                   # misaligned
+    (dict(degree=0), ann.ANN_EINVAL),
+    (dict(n_entry=0), ann.ANN_EINVAL),
+    (dict(n_entry=513), ann.ANN_EINVAL),
+    (dict(entry_mode=3), ann.ANN_EINVAL),
+    (dict(entry_mode=1), ann.ANN_EINVAL),                       # routed without centroids
+    (dict(entry_mode=1, centroids=FAKE, cluster_offsets=FAKE, n_clusters=4, route_c=5), ann.ANN_EINVAL),
+    (dict(entry_mode=1, centroids=FAKE, cluster_offsets=FAKE, n_clusters=40, route_c=9), ann.ANN_EINVAL),
+    (dict(dim=512, row_stride_bytes=512), ann.ANN_EUNSUPPORTED),  # uint8 rows above 256 bytes: no variant built
+])
+def test_load_rejects(kw, code):
+    rc, h = load(desc(**kw))
+    assert rc == code and not h.value
+    assert ann.ann_last_error()
+
+
+def test_search_argument_errors_and_empty_batch():
+    L = ann.lib()
+    rc, h = load(desc())
+    assert rc == ann.ANN_OK
+
+    def search(nq=10, k=10, itopk=64, width=1, max_iters=5, q=FAKE, ids=FAKE, dists=FAKE):
+        return L.ann_search(h, q, nq, k, itopk, width, max_iters, ids, dists, None)
+
+    assert search(nq=0) == ann.ANN_OK                   # nothing to do, nothing launched
+    assert search(nq=0, q=None, ids=None, dists=None) == ann.ANN_OK
+    assert search(nq=-1) == ann.ANN_EINVAL
+    assert search(k=0) == ann.ANN_EINVAL
+    assert search(k=65) == ann.ANN_EINVAL               # k above itopk
+    assert search(max_iters=-1) == ann.ANN_EINVAL
+    assert search(itopk=513, k=10) == ann.ANN_EUNSUPPORTED
+    assert search(width=17) == ann.ANN_EUNSUPPORTED     # 17 * 32 neighbours per round: above 512
+    assert search(width=0) == ann.ANN_EUNSUPPORTED
+    assert search(q=None) == ann.ANN_EINVAL
+    assert search(ids=None) == ann.ANN_EINVAL
+    assert search(dists=None) == ann.ANN_EINVAL
+    assert search(q=FAKE + 4) == ann.ANN_EINVAL
+    assert "aligned" in ann.ann_last_error()
+    assert L.ann_route(h, FAKE, 4, FAKE, None) == ann.ANN_EINVAL  # not a routed index
+    assert L.ann_free(h) == ann.ANN_OK
+    assert L.ann_search(None, FAKE, 1, 1, 1, 1, 1, FAKE, FAKE, None) == ann.ANN_EINVAL
+
+
+def test_binding_refuses_host_tensors():
+    import torch
+
+    x = torch.zeros((100, 128), dtype=torch.uint8)
+    g = torch.zeros((100, 32), dtype=torch.int32)
+    with pytest.raises(ValueError):
+        ann.ann_index_load(x, g)

@@ -1,0 +1,294 @@
+"""GPU library against the CPU oracle, element by element, on the same seeded inputs.
+
+uint8 data: ids and int32 keys must be bit-identical, and so must the number of
+rounds and of graph rows read (the search takes the same path).  Float data: keys
+within 1e-5 (fp32) / 1e-3 (fp16 inputs, fp32 accumulation) relative, ids identical
+except at near-ties inside that tolerance.
+"""
+import os
+
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+NP_DT = {"u8": np.uint8, "f16": np.float16, "f32": np.float32}
+TOL = {"f16": 1e-3, "f32": 1e-5}
+
+
+@pytest.fixture(scope="module")
+def torch_cuda():
+    import torch
+
+    if not torch.cuda.is_available():
+        pytest.fail("these tests need the MI355X (run with -m 'not gpu' elsewhere)")
+    return torch
+
+
+def gpu_search(torch, x, g, q, k, itopk, width, max_iters, metric=0, n_entry=32, entry_mode=0, seed=0, centroids=None,
+               offsets=None, route_c=0, want_counters=True):
+    from paper_2512_02278_amd import ann
+
+    dev = "cuda:0"
+    # x may be a strided view (padded rows): move the padded buffer and re-slice
+    if x.strides[0] != x.shape[1] * x.itemsize:
+        base = x.base
+        xt = torch.from_numpy(np.ascontiguousarray(base)).to(dev)[:, : x.shape[1]]
+    else:
+        xt = torch.from_numpy(np.ascontiguousarray(x)).to(dev)
+    gt = torch.from_numpy(np.ascontiguousarray(g, dtype=np.int32)).to(dev)
+    qt = torch.from_numpy(np.ascontiguousarray(q)).to(dev)
+    ct = None if centroids is None else torch.from_numpy(np.ascontiguousarray(centroids)).to(dev)
+    ot = None if offsets is None else torch.from_numpy(np.ascontiguousarray(offsets, dtype=np.int64)).to(dev)
+    h = ann.ann_index_load(xt, gt, metric=metric, n_entry=n_entry, entry_mode=entry_mode, seed=seed, centroids=ct,
+                           cluster_offsets=ot, route_c=route_c)
+    cnt = torch.zeros((q.shape[0], 4), dtype=torch.int32, device=dev) if want_counters else None
+    ids, dists = ann.ann_search(h, qt, k, itopk, width, max_iters, counters=cnt)
+    torch.cuda.synchronize()
+    ann.ann_free(h)
+    return ids.cpu().numpy(), dists.cpu().numpy(), (cnt.cpu().numpy() if want_counters else None)
+
+
+def check_exact(oracle, torch, x, g, q, k, itopk, width, max_iters, **kw):
+    ix = oracle.Index(x, g, metric=kw.get("metric", 0), n_entry=kw.get("n_entry", 32),
+                      entry_mode=kw.get("entry_mode", 0), seed=kw.get("seed", 0), centroids=kw.get("centroids"),
+                      cluster_offsets=kw.get("offsets"), route_c=kw.get("route_c", 0))
+    oi, od, oc = oracle.search(ix, q, k, itopk, width, max_iters)
+    gi, gd, gc = gpu_search(torch, x, g, q, k, itopk, width, max_iters, **kw)
+    assert np.array_equal(gi, oi), f"ids differ in {np.argwhere(gi != oi)[:5].tolist()}"
+    assert np.array_equal(gd, od)
+    assert np.array_equal(gc[:, 0], oc["iters"]) and np.array_equal(gc[:, 2], oc["n_parents"])
+    assert (gc[:, 1] >= oc["n_dist"]).all()  # a forgetful visited table may score a node again, never fewer
+    return gc, oc
+
+
+def check_float(oracle, torch, x, g, q, k, itopk, width, max_iters, tol, min_identical=0.9, **kw):
+    ix = oracle.Index(x, g, metric=kw.get("metric", 0), n_entry=kw.get("n_entry", 32),
+                      entry_mode=kw.get("entry_mode", 0), seed=kw.get("seed", 0), centroids=kw.get("centroids"),
+                      cluster_offsets=kw.get("offsets"), route_c=kw.get("route_c", 0))
+    oi, od, _ = oracle.search(ix, q, k, itopk, width, max_iters)
+    gi, gd, _ = gpu_search(torch, x, g, q, k, itopk, width, max_iters, **kw)
+    assert np.array_equal(gi < 0, oi < 0)
+    real = gi >= 0
+    # reported key = the oracle's key of the reported id, within tolerance
+    gk = oracle.keys(x, q, gi, kw.get("metric", 0))
+    scale = np.maximum(np.abs(gk), 1e-30)
+    assert (np.abs(gd.astype(np.float64) - gk)[real] <= tol * scale[real]).all()
+    assert np.isinf(gd[~real]).all()
+    # rank by rank, the ids found are as good as the oracle's within tolerance
+    gs = np.sort(np.where(real, gk, np.inf), axis=1)
+    os_ = np.where(oi >= 0, od.astype(np.float64), np.inf)
+    both = np.isfinite(gs) & np.isfinite(os_)
+    assert (np.abs(gs - os_)[both] <= tol * np.maximum(np.abs(os_[both]), 1e-30)).all()
+    for i in range(len(q)):
+        ids = gi[i][gi[i] >= 0]
+        assert len(set(ids.tolist())) == len(ids)
+    identical = float((gi == oi).all(1).mean())
+    assert identical >= min_identical, identical
+    return identical
+
+
+# ----------------------------------------------------------------------------- tiny config (config 1)
+@pytest.fixture(scope="module")
+def tiny():
+    from paper_2512_02278_amd import inputs
+
+    part = inputs.sift_like(10_000, 100)
+    inputs.knn_graph_exact(part, 32)
+    q = inputs.sift_like_queries(part, 100)
+    return part, q
+
+
+def test_tiny_config_uniform_entries(oracle, torch_cuda, tiny):
+    part, q = tiny
+    check_exact(oracle, torch_cuda, part.vectors.numpy(), part.graph.numpy(), q.numpy(), 10, 64, 1, 50, n_entry=32,
+                seed=20251204)
+
+
+def test_tiny_config_routed_entries(oracle, torch_cuda, tiny):
+    part, q = tiny
+    gc, oc = check_exact(oracle, torch_cuda, part.vectors.numpy(), part.graph.numpy(), q.numpy(), 10, 64, 1, 50,
+                         n_entry=32, seed=20251204, entry_mode=1, centroids=part.centres.numpy(),
+                         offsets=part.offsets.numpy(), route_c=2)
+    assert oc["iters"].mean() > 10
+
+
+def test_same_call_twice_gives_the_same_bytes(torch_cuda, tiny):
+    part, q = tiny
+    a = gpu_search(torch_cuda, part.vectors.numpy(), part.graph.numpy(), q.numpy(), 10, 64, 2, 50, seed=3)
+    b = gpu_search(torch_cuda, part.vectors.numpy(), part.graph.numpy(), q.numpy(), 10, 64, 2, 50, seed=3)
+    assert all(np.array_equal(u, v) for u, v in zip(a, b))
+
+
+# ----------------------------------------------------------------------------- random graphs, every list variant
+def clustered(rng, n, dim, dt, n_centres=12, spread=14.0):
+    cen = rng.integers(30, 226, (n_centres, dim)).astype(np.float64)
+    lab = np.sort(rng.integers(0, n_centres, n))
+    x = cen[lab] + rng.standard_normal((n, dim)) * spread
+    off = np.searchsorted(lab, np.arange(n_centres + 1)).astype(np.int64)
+    if dt == "u8":
+        return np.clip(np.rint(x), 0, 255).astype(np.uint8), np.clip(np.rint(cen), 0, 255).astype(np.uint8), off
+    return (x / 64).astype(NP_DT[dt]), (cen / 64).astype(NP_DT[dt]), off
+
+
+def knn_graph(x, degree, metric=0):
+    xf = x.astype(np.float64)
+    if metric == 0:
+        sq = (xf * xf).sum(1)
+        d = sq[:, None] + sq[None, :] - 2 * xf @ xf.T
+    else:
+        d = -(xf @ xf.T)
+    np.fill_diagonal(d, np.inf)
+    return np.argsort(d, 1, kind="stable")[:, :degree].astype(np.int32)
+
+
+def queries_near(rng, x, nq, dt):
+    q = x[rng.integers(0, len(x), nq)].astype(np.float64)
+    if dt == "u8":
+        return np.clip(np.rint(q + rng.integers(-8, 9, q.shape)), 0, 255).astype(np.uint8)
+    return (q + rng.standard_normal(q.shape) * 0.05).astype(NP_DT[dt])
+
+
+@pytest.mark.parametrize("itopk,width,degree,k,n_entry", [
+    (64, 1, 32, 10, 32),     # list 64, batch 32
+    (33, 2, 24, 33, 7),      # odd sizes, k = itopk, degree not a power of two
+    (128, 4, 32, 10, 32),    # the 1M / 100M configs' shape
+    (100, 3, 40, 16, 100),   # batch 120, 100 entries
+    (192, 4, 32, 10, 32),
+    (256, 4, 64, 10, 32),    # the Deep-like config's shape
+    (256, 8, 64, 100, 32),   # the text-like config's shape: 512 neighbours per round
+    (512, 2, 48, 50, 500),
+    (1, 1, 16, 1, 1),        # a plain greedy walk
+])
+def test_uint8_bit_exact_across_list_variants(oracle, torch_cuda, itopk, width, degree, k, n_entry):
+    rng = np.random.default_rng(itopk * 131 + width)
+    x, cen, off = clustered(rng, 6000, 128, "u8")
+    g = knn_graph(x, degree)
+    g[rng.random(g.shape) < 0.05] = -1                       # empty slots
+    g[rng.random(g.shape) < 0.02] = 6000 + 17                # ids outside the partition
+    dup = rng.random(g.shape[0]) < 0.1
+    g[dup, 1] = g[dup, 0]                                    # the same neighbour twice in a row
+    q = queries_near(rng, x, 150, "u8")
+    check_exact(oracle, torch_cuda, x, g, q, k, itopk, width, 80, n_entry=n_entry, seed=itopk)
+    check_exact(oracle, torch_cuda, x, g, q, k, itopk, width, 80, n_entry=n_entry, seed=itopk, entry_mode=1,
+                centroids=cen, offsets=off, route_c=3)
+
+
+def test_uint8_heavy_ties_and_inner_product(oracle, torch_cuda):
+    rng = np.random.default_rng(5)
+    x = rng.integers(0, 4, (5000, 64), dtype=np.uint8)       # 2-bit coordinates: many equal keys
+    g = rng.integers(0, 5000, (5000, 20), dtype=np.int32)
+    q = rng.integers(0, 4, (200, 64), dtype=np.uint8)
+    for metric in (0, 1):
+        check_exact(oracle, torch_cuda, x, g, q, 20, 96, 3, 60, metric=metric, n_entry=16, seed=9)
+
+
+@pytest.mark.parametrize("dim", [16, 48, 128, 160, 256])
+def test_uint8_dims_and_padded_rows(oracle, torch_cuda, dim):
+    rng = np.random.default_rng(dim)
+    buf = rng.integers(0, 256, (3000, dim + 32), dtype=np.uint8)
+    x = buf[:, :dim]                                          # row stride dim + 32 bytes
+    g = rng.integers(0, 3000, (3000, 16), dtype=np.int32)
+    q = rng.integers(0, 256, (64, dim), dtype=np.uint8)
+    check_exact(oracle, torch_cuda, x, g, q, 10, 64, 2, 40, n_entry=8, seed=1)
+
+
+def test_small_visited_table_forces_resets(oracle, torch_cuda, monkeypatch):
+    """With the smallest table the kernel forgets visited nodes every few rounds; the
+    result must not change, only more rows are gathered."""
+    rng = np.random.default_rng(77)
+    x, cen, off = clustered(rng, 8000, 128, "u8", n_centres=4)
+    g = knn_graph(x, 32)
+    q = queries_near(rng, x, 200, "u8")
+    monkeypatch.setenv("ANN_HASH_BITS_BIAS", "-1")
+    gc, oc = check_exact(oracle, torch_cuda, x, g, q, 10, 128, 4, 100, n_entry=32, seed=2, entry_mode=1,
+                         centroids=cen, offsets=off, route_c=1)
+    assert gc[:, 3].max() >= 1 and (gc[:, 1] > oc["n_dist"]).any()
+
+
+def test_edge_cases(oracle, torch_cuda):
+    # one node, no edges; fewer reachable nodes than k; a single query; max_iters = 0
+    x = np.full((1, 128), 7, np.uint8)
+    g = np.full((1, 4), -1, np.int32)
+    q = np.zeros((1, 128), np.uint8)
+    check_exact(oracle, torch_cuda, x, g, q, 5, 8, 1, 10, n_entry=3, seed=1)
+    rng = np.random.default_rng(1)
+    x = rng.integers(0, 256, (40, 128), dtype=np.uint8)
+    g = np.full((40, 4), -1, np.int32)
+    q = rng.integers(0, 256, (9, 128), dtype=np.uint8)
+    check_exact(oracle, torch_cuda, x, g, q, 10, 16, 2, 10, n_entry=4, seed=2)   # no edges: only entries
+    g = rng.integers(0, 40, (40, 4), dtype=np.int32)
+    check_exact(oracle, torch_cuda, x, g, q, 10, 16, 2, 0, n_entry=4, seed=2)    # max_iters = 0
+    check_exact(oracle, torch_cuda, x, g, q, 40, 64, 3, 200, n_entry=4, seed=2)  # itopk above n
+
+
+# ----------------------------------------------------------------------------- float data
+@pytest.mark.parametrize("dt,dim,metric,itopk,width,degree,k", [
+    ("f32", 96, 0, 256, 4, 64, 10),    # Deep-like shape
+    ("f32", 96, 1, 64, 2, 32, 10),
+    ("f32", 256, 0, 64, 2, 32, 10),    # 1024-byte rows: the 32-lane variant
+    ("f16", 768, 1, 256, 8, 64, 100),  # text-like shape
+    ("f16", 768, 0, 128, 4, 32, 10),
+    ("f16", 64, 0, 64, 1, 16, 10),
+])
+def test_float_parity(oracle, torch_cuda, dt, dim, metric, itopk, width, degree, k):
+    rng = np.random.default_rng(dim + metric)
+    x, cen, off = clustered(rng, 4000, dim, dt)
+    if metric == 1:
+        x = (x.astype(np.float64) / np.linalg.norm(x.astype(np.float64), axis=1, keepdims=True)).astype(NP_DT[dt])
+    g = knn_graph(x, degree, metric)
+    q = queries_near(rng, x, 120, dt)
+    same = check_float(oracle, torch_cuda, x, g, q, k, itopk, width, 100, TOL[dt], metric=metric, n_entry=32, seed=4)
+    print(f"{dt} dim={dim} metric={metric}: {same:.3f} of the queries have identical id lists")
+
+
+def test_route_matches_oracle(oracle, torch_cuda):
+    from paper_2512_02278_amd import ann
+
+    torch = torch_cuda
+    rng = np.random.default_rng(3)
+    for dt, dim in (("u8", 128), ("f32", 96), ("f16", 768)):
+        x, cen, off = clustered(rng, 2000, dim, dt, n_centres=300)
+        q = queries_near(rng, x, 100, dt)
+        want = oracle.route(cen, q, 4, 0)
+        xt, ct = torch.from_numpy(x).cuda(), torch.from_numpy(cen).cuda()
+        gt = torch.zeros((2000, 4), dtype=torch.int32, device="cuda")
+        h = ann.ann_index_load(xt, gt, entry_mode=1, centroids=ct, cluster_offsets=torch.from_numpy(off).cuda(),
+                               route_c=4)
+        got = ann.ann_route(h, torch.from_numpy(q).cuda()).cpu().numpy()
+        ann.ann_free(h)
+        if dt == "u8":
+            assert np.array_equal(got, want)
+        else:
+            assert (got == want).mean() > 0.98
+
+
+# ----------------------------------------------------------------------------- full-size config, sampled
+def test_one_million_config_sampled_against_oracle(oracle, torch_cuda):
+    """Config 2 at full size in the bench's launch shape (10 000 queries in one call); the
+    oracle recomputes the first 200 queries of the batch one by one."""
+    from paper_2512_02278_amd import ann, inputs
+
+    torch = torch_cuda
+    part = inputs.sift_like(1_000_000, 1000, device="cuda")
+    inputs.knn_graph_clustered(part, 32)
+    q = inputs.sift_like_queries(part, 10_000)
+    h = ann.ann_index_load(part.vectors, part.graph, n_entry=32, entry_mode=1, seed=20251204, centroids=part.centres,
+                           cluster_offsets=part.offsets, route_c=1)
+    cnt = torch.zeros((10_000, 4), dtype=torch.int32, device="cuda")
+    ids, dists = ann.ann_search(h, q, 10, 128, 4, 100, counters=cnt)
+    torch.cuda.synchronize()
+    ann.ann_free(h)
+    ix = oracle.Index(part.vectors.cpu().numpy(), part.graph.cpu().numpy(), n_entry=32, entry_mode=1, seed=20251204,
+                      centroids=part.centres.cpu().numpy(), cluster_offsets=part.offsets.cpu().numpy(), route_c=1)
+    oi, od, oc = oracle.search(ix, q[:200].cpu().numpy(), 10, 128, 4, 100)
+    assert np.array_equal(ids[:200].cpu().numpy(), oi) and np.array_equal(dists[:200].cpu().numpy(), od)
+    assert np.array_equal(cnt[:200, 0].cpu().numpy(), oc["iters"])
+    # properties that hold for every query of the batch
+    ids_all = ids.cpu().numpy()
+    d_all = dists.cpu().numpy()
+    assert (np.diff(d_all.astype(np.int64), axis=1) >= 0).all()
+    assert (ids_all >= 0).all() and (ids_all < 1_000_000).all()
+    assert all(len(set(r.tolist())) == 10 for r in ids_all[::97])
+    gt = inputs.ground_truth(part, q[:500], 10)
+    assert inputs.recall(ids[:500], gt) > 0.95
