@@ -1,0 +1,253 @@
+"""Benchmark of the search hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--nq N]
+
+A step is one ann_search call (routing + beam search, every stage of the hot path)
+over one batch of synthetic queries that already sits in HBM.  The default workload
+is the 100M-vector uint8 partition ("one GPU's tenth of a billion-scale SIFT-like
+index").  Prints ONE JSON line; progress goes to stderr.
+
+The line carries: queries/s at the smallest itopk whose recall@10 reaches 0.95,
+recall, bytes per query (algorithmic, from the oracle's counters; actual, from the
+kernel's), the roofline of the beam-search kernel (HBM), a batch-size sweep, and the
+CPU oracle timed on this machine's host cores on a sample of the same batch, which is
+also checked bit for bit against the GPU's answers.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E, published peak
+
+WORKLOADS = {
+    # name: generator settings and search parameters (benchmark configs)
+    "sift100m": dict(kind="sift", n=100_000_000, centres=16384, dim=128, degree=32, nq=1_000_000, k=10, width=4,
+                     max_iters=200, itopk_sweep=(128, 160, 192, 224, 256), sweep=(1_000, 10_000, 100_000, 1_000_000),
+                     text="100M x 128 uint8 SIFT-like partition, 16384 centres, degree-32 cluster-restricted kNN graph"),
+    "sift1m": dict(kind="sift", n=1_000_000, centres=1000, dim=128, degree=32, nq=10_000, k=10, width=4, max_iters=100,
+                   itopk_sweep=(128, 160, 192, 256), sweep=(1_000, 10_000),
+                   text="1M x 128 uint8 SIFT-like index, 1000 centres, degree-32 cluster-restricted kNN graph"),
+    "tiny": dict(kind="sift", n=10_000, centres=100, dim=128, degree=32, nq=100, k=10, width=1, max_iters=50,
+                 itopk_sweep=(64,), sweep=(100,), exact_graph=True,
+                 text="10k x 128 uint8 SIFT-like index, 100 centres, exact degree-32 kNN graph"),
+}
+SEED = 20251202
+
+
+def log(msg: str) -> None:
+    print(f"[bench {time.strftime('%H:%M:%S')}] {msg}", file=sys.stderr, flush=True)
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="sift100m", choices=sorted(WORKLOADS))
+    ap.add_argument("--nq", type=int, default=0, help="queries per step (default: the workload's batch)")
+    ap.add_argument("--oracle-seconds", type=float, default=15.0, help="wall-clock aim for the CPU oracle sample")
+    ap.add_argument("--no-oracle", action="store_true", help="skip the CPU baseline and the sampled parity check")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build covers one GPU's partition; it has no multi-GPU path, run with --gpus 1",
+              file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    from paper_2512_02278_amd import ann, inputs, metrics
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    ann.lib()  # fail early if the library is not built
+    dev = "cuda:0"
+    w = WORKLOADS[args.workload]
+    nq = args.nq or w["nq"]
+    k, width, max_iters, degree = w["k"], w["width"], w["max_iters"], w["degree"]
+
+    # ------------------------------------------------------------------ inputs (resident in HBM)
+    t0 = time.time()
+    part = inputs.sift_like(w["n"], w["centres"], dim=w["dim"], seed=SEED, device=dev)
+    if w.get("exact_graph"):
+        inputs.knn_graph_exact(part, degree)
+    else:
+        inputs.knn_graph_clustered(part, degree, progress=(lambda c, t: log(f"graph: cluster {c}/{t}"),
+                                                           max(1, w["centres"] // 8)))
+    nq_max = max(nq, max(w["sweep"]))
+    queries = inputs.sift_like_queries(part, nq_max, seed=SEED + 1)
+    torch.cuda.synchronize()
+    log(f"index and {nq_max} queries generated in {time.time() - t0:.1f} s")
+    n_gt = min(2000, nq)
+    t0 = time.time()
+    truth = inputs.ground_truth(part, queries[:n_gt], k)
+    torch.cuda.synchronize()
+    log(f"exact ground truth for {n_gt} queries in {time.time() - t0:.1f} s")
+
+    h = ann.ann_index_load(part.vectors, part.graph, metric=ann.ANN_L2, n_entry=32, entry_mode=ann.ANN_ENTRY_ROUTED,
+                           seed=SEED + 2, centroids=part.centres, cluster_offsets=part.offsets, route_c=1)
+    row_bytes = w["dim"] * part.vectors.element_size()
+
+    # ------------------------------------------------------------------ smallest itopk with recall >= 0.95
+    recall_by_itopk = {}
+    itopk = None
+    for cand in w["itopk_sweep"]:
+        ids, _ = ann.ann_search(h, queries[:n_gt], k, cand, width, max_iters)
+        torch.cuda.synchronize()
+        recall_by_itopk[cand] = round(inputs.recall(ids, truth), 4)
+        if recall_by_itopk[cand] >= 0.95:
+            itopk = cand
+            break
+    log(f"recall@{k} by itopk: {recall_by_itopk}")
+    target_met = itopk is not None
+    if itopk is None:
+        itopk = w["itopk_sweep"][-1]
+
+    q = queries[:nq]
+    out_ids = torch.empty((nq, k), dtype=torch.int32, device=dev)
+    out_d = torch.empty((nq, k), dtype=torch.int32, device=dev)
+
+    # ------------------------------------------------------------------ timed steps: whole hot path
+    for _ in range(args.warmup):
+        ann.ann_search(h, q, k, itopk, width, max_iters, out_ids=out_ids, out_dists=out_d)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        ann.ann_search(h, q, k, itopk, width, max_iters, out_ids=out_ids, out_dists=out_d)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall / args.steps * 1e3
+    qps = nq / (wall / args.steps)
+    rec = inputs.recall(out_ids[:n_gt], truth)
+    log(f"{nq} queries/step, itopk {itopk}: {ms_per_step:.2f} ms/step, {qps:.3e} q/s, recall@{k} {rec:.4f}")
+
+    # ------------------------------------------------------------------ the two kernels on their own (HIP events on the launch stream)
+    def event_ms(fn, reps):
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+        for a, b in evs:
+            a.record()
+            fn()
+            b.record()
+        torch.cuda.synchronize()
+        return sum(a.elapsed_time(b) for a, b in evs) / reps
+
+    routes = ann.ann_route(h, q)
+    route_ms = event_ms(lambda: ann.ann_route(h, q, out_clusters=routes), args.steps)
+    search_ms = event_ms(lambda: ann.ann_search(h, q, k, itopk, width, max_iters, out_ids=out_ids, out_dists=out_d,
+                                                routes=routes), args.steps)
+    counters = torch.zeros((nq, 4), dtype=torch.int32, device=dev)
+    ann.ann_search(h, q, k, itopk, width, max_iters, out_ids=out_ids, out_dists=out_d, counters=counters)
+    torch.cuda.synchronize()
+    cm = counters.double().mean(0).tolist()
+    actual_bq = metrics.algorithmic_bytes_per_query(cm[1], cm[2], row_bytes, degree, row_bytes, k)
+    log(f"kernels: route {route_ms:.3f} ms, beam search {search_ms:.3f} ms; per query: rounds {cm[0]:.1f}, rows "
+        f"gathered {cm[1]:.0f}, graph rows {cm[2]:.0f}, table resets {cm[3]:.2f}")
+
+    # ------------------------------------------------------------------ batch-size sweep (whole hot path)
+    sweep = {}
+    for b in w["sweep"]:
+        if b > nq_max:
+            continue
+        qb = queries[:b]
+        reps = max(3, min(20, int(2e6 // b)))
+        for _ in range(2):
+            ann.ann_search(h, qb, k, itopk, width, max_iters, out_ids=out_ids[:b], out_dists=out_d[:b])
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            ann.ann_search(h, qb, k, itopk, width, max_iters, out_ids=out_ids[:b], out_dists=out_d[:b])
+        torch.cuda.synchronize()
+        sweep[str(b)] = round(b * reps / (time.perf_counter() - t0), 1)
+    log(f"q/s by batch size: {sweep}")
+    # leave the outputs of the full batch in place for the parity check
+    ann.ann_search(h, q, k, itopk, width, max_iters, out_ids=out_ids, out_dists=out_d)
+    torch.cuda.synchronize()
+
+    # ------------------------------------------------------------------ CPU oracle: baseline, parity sample, algorithmic counters
+    cpu_baseline = None
+    parity = None
+    algo = dict(n_dist=None, n_parents=None)
+    if not args.no_oracle:
+        import oracle
+
+        t0 = time.time()
+        ix = oracle.Index(part.vectors.cpu().numpy(), part.graph.cpu().numpy(), n_entry=32, entry_mode=1, seed=SEED + 2,
+                          centroids=part.centres.cpu().numpy(), cluster_offsets=part.offsets.cpu().numpy(), route_c=1)
+        log(f"index copied to host in {time.time() - t0:.1f} s")
+        qh = q.cpu().numpy()
+        cores = oracle.threads()
+        probe = min(nq, 256)
+        t0 = time.perf_counter()
+        oracle.search(ix, qh[:probe], k, itopk, width, max_iters)
+        per_q = (time.perf_counter() - t0) / probe
+        sample = int(max(probe, min(nq, args.oracle_seconds / per_q)))
+        t0 = time.perf_counter()
+        oi, od, oc = oracle.search(ix, qh[:sample], k, itopk, width, max_iters)
+        cpu_s = time.perf_counter() - t0
+        cpu_baseline = {"value": round(sample / cpu_s, 1), "unit": "queries/s", "cores": cores, "kind": "oracle",
+                        "sample": f"first {sample} queries of the timed batch, same index, itopk {itopk}; "
+                                  f"{cpu_s:.1f} s on {cores} threads"}
+        same = bool(np.array_equal(out_ids[:sample].cpu().numpy(), oi) and
+                    np.array_equal(out_d[:sample].cpu().numpy(), od))
+        parity = {"queries_checked": sample, "bit_identical": same}
+        algo = dict(n_dist=float(oc["n_dist"].mean()), n_parents=float(oc["n_parents"].mean()))
+        log(f"oracle: {sample} queries in {cpu_s:.1f} s on {cores} threads; GPU bit-identical: {same}")
+        del ix
+
+    ann.ann_free(h)
+
+    # ------------------------------------------------------------------ roofline of the dominant kernel
+    if algo["n_dist"] is not None:
+        algo_bq = metrics.algorithmic_bytes_per_query(algo["n_dist"], algo["n_parents"], row_bytes, degree, row_bytes, k)
+    else:
+        algo_bq = None
+    traffic = read_traffic(args.workload)
+    roofline = None
+    if algo_bq is not None:
+        achieved = algo_bq * nq / (search_ms * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "kernel": "beam_search_kernel", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
+                    "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
+                    "kernel_ms": round(search_ms, 3), "algorithmic_bytes_per_launch": round(algo_bq * nq)}
+
+    line = {
+        "metric": "queries/sec at recall@10>=0.95 on 1 MI355X", "value": round(qps, 1), "unit": "queries/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u8", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: {w['text']}; {nq} queries per step in drawn order, k={k}, "
+                               f"itopk={itopk}, width={width}, max_iters={max_iters}, 32 routed entries (route_c=1)",
+                   "itopk": itopk, "queries_per_step": nq},
+        "recall_at_10": round(rec, 4), "recall_target_met": target_met, "recall_by_itopk": recall_by_itopk,
+        "bytes_per_query": {"algorithmic": None if algo_bq is None else round(algo_bq), "gathered": round(actual_bq)},
+        "per_query": {"rounds": round(cm[0], 2), "rows_gathered": round(cm[1], 1), "graph_rows": round(cm[2], 1),
+                      "rows_scored_by_oracle": algo["n_dist"]},
+        "kernel_ms": {"route_kernel": round(route_ms, 3), "beam_search_kernel": round(search_ms, 3)},
+        "qps_by_batch": sweep, "parity": parity, "roofline": roofline, "cpu_baseline": cpu_baseline,
+    }
+    print(json.dumps(line), flush=True)
+    return 0
+
+
+def read_traffic(workload: str):
+    """HBM bytes per launch of the beam-search kernel, from the committed rocprofv3 --pmc
+    summary of this workload (profiles/), or None if none has been recorded."""
+    path = os.path.join(ROOT, "profiles", f"beam_search_kernel_{workload}_pmc.txt")
+    try:
+        for ln in open(path):
+            if ln.startswith("traffic_bytes_per_launch"):
+                return float(ln.split("=")[1])
+    except OSError:
+        pass
+    return None
+
+
+if __name__ == "__main__":
+    sys.exit(main())

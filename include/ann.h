@@ -117,6 +117,17 @@ int ann_search_counters(ann_index_t* handle, const void* queries, int64_t nq, in
  */
 int ann_route(ann_index_t* handle, const void* queries, int64_t nq, int32_t* out_clusters, void* stream);
 
+/*
+ * The search step alone for a routed index, with the routing already done: `routes`
+ * (DEVICE, nq*route_c int32, as written by ann_route for the same queries) replaces
+ * the internal routing pass and no scratch is allocated.  Stage 1 and stage 3 of the
+ * paper's workflow (Sec. 3.1) can so be issued separately, e.g. on different streams
+ * for consecutive batches.  out_counters may be NULL.
+ */
+int ann_search_routed(ann_index_t* handle, const void* queries, int64_t nq, const int32_t* routes, int k, int itopk,
+                      int width, int max_iters, int32_t* out_ids, void* out_dists, int32_t* out_counters,
+                      void* stream);
+
 /* Releases the handle (host memory only).  NULL is accepted. */
 int ann_free(ann_index_t* handle);
 

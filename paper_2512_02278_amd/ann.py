@@ -21,8 +21,8 @@ ANN_OK, ANN_EINVAL, ANN_EUNSUPPORTED, ANN_ENOMEM, ANN_EHIP = 0, -1, -2, -3, -4
 
 _DTYPES = {torch.uint8: ANN_U8, torch.float16: ANN_F16, torch.float32: ANN_F32}
 
-EXPORTS = ("ann_index_load", "ann_search", "ann_search_counters", "ann_route", "ann_free", "ann_last_error",
-           "ann_lds_bytes")
+EXPORTS = ("ann_index_load", "ann_search", "ann_search_counters", "ann_search_routed", "ann_route", "ann_free",
+           "ann_last_error", "ann_lds_bytes")
 
 
 class ann_index_desc_t(ctypes.Structure):
@@ -58,6 +58,8 @@ def lib() -> ctypes.CDLL:
         L.ann_search.restype = ctypes.c_int
         L.ann_search_counters.argtypes = [vp, vp, i64, i32, i32, i32, i32, vp, vp, vp, vp]
         L.ann_search_counters.restype = ctypes.c_int
+        L.ann_search_routed.argtypes = [vp, vp, i64, vp, i32, i32, i32, i32, vp, vp, vp, vp]
+        L.ann_search_routed.restype = ctypes.c_int
         L.ann_route.argtypes = [vp, vp, i64, vp, vp]
         L.ann_route.restype = ctypes.c_int
         L.ann_free.argtypes = [vp]
@@ -132,10 +134,12 @@ def _queries_ok(h: Handle, queries: torch.Tensor):
 
 
 def ann_search(h: Handle, queries: torch.Tensor, k: int, itopk: int, width: int, max_iters: int,
-               out_ids: torch.Tensor = None, out_dists: torch.Tensor = None, stream=None, counters: torch.Tensor = None):
+               out_ids: torch.Tensor = None, out_dists: torch.Tensor = None, stream=None, counters: torch.Tensor = None,
+               routes: torch.Tensor = None):
     """Enqueues the search on `stream` (default: torch's current stream); returns (out_ids, out_dists).
 
-    With `counters` (int32 [nq, 4]) the call goes to ann_search_counters."""
+    With `counters` (int32 [nq, 4]) the call goes to ann_search_counters; with `routes`
+    (int32 [nq, route_c] from ann_route) it goes to ann_search_routed."""
     _queries_ok(h, queries)
     nq = queries.shape[0]
     dd = torch.int32 if h.dtype == torch.uint8 else torch.float32
@@ -147,12 +151,18 @@ def ann_search(h: Handle, queries: torch.Tensor, k: int, itopk: int, width: int,
         raise ValueError("out_ids / out_dists have the wrong dtype or size")
     if not (out_ids.is_contiguous() and out_dists.is_contiguous()):
         raise ValueError("outputs must be contiguous")
-    if counters is None:
+    if counters is not None and (counters.dtype != torch.int32 or counters.numel() != nq * 4 or not counters.is_contiguous()):
+        raise ValueError("counters must be a contiguous int32 [nq, 4] tensor")
+    if routes is not None:
+        if routes.dtype != torch.int32 or routes.numel() != nq * h.route_c or not routes.is_contiguous():
+            raise ValueError("routes must be a contiguous int32 [nq, route_c] tensor")
+        rc = lib().ann_search_routed(h.ptr, _dev_ptr(queries, "queries"), nq, _dev_ptr(routes, "routes"), k, itopk, width,
+                                     max_iters, _dev_ptr(out_ids, "out_ids"), _dev_ptr(out_dists, "out_dists"),
+                                     _dev_ptr(counters, "counters"), _stream(stream))
+    elif counters is None:
         rc = lib().ann_search(h.ptr, _dev_ptr(queries, "queries"), nq, k, itopk, width, max_iters,
                               _dev_ptr(out_ids, "out_ids"), _dev_ptr(out_dists, "out_dists"), _stream(stream))
     else:
-        if counters.dtype != torch.int32 or counters.numel() != nq * 4 or not counters.is_contiguous():
-            raise ValueError("counters must be a contiguous int32 [nq, 4] tensor")
         rc = lib().ann_search_counters(h.ptr, _dev_ptr(queries, "queries"), nq, k, itopk, width, max_iters,
                                        _dev_ptr(out_ids, "out_ids"), _dev_ptr(out_dists, "out_dists"),
                                        _dev_ptr(counters, "counters"), _stream(stream))

@@ -184,30 +184,35 @@ extern "C" int ann_route(ann_index_t* h, const void* queries, int64_t nq, int32_
     return ANN_OK;
 }
 
-extern "C" int ann_search_counters(ann_index_t* h, const void* queries, int64_t nq, int k, int itopk, int width,
-                                   int max_iters, int32_t* out_ids, void* out_dists, int32_t* out_counters,
-                                   void* stream_) {
+namespace {
+
+// Checks the arguments of a search and launches it; `route` is null for uniform entries.
+int search_impl(ann_index_t* h, const void* queries, int64_t nq, const int32_t* route, bool route_given, int k,
+                int itopk, int width, int max_iters, int32_t* out_ids, void* out_dists, int32_t* out_counters,
+                hipStream_t stream) {
     if (!h || h->magic != kMagic) return fail(ANN_EINVAL, "ann_search: not a live handle");
     if (nq < 0) return fail(ANN_EINVAL, "ann_search: nq = %lld", (long long)nq);
     if (k < 1 || k > itopk) return fail(ANN_EINVAL, "ann_search: k = %d outside 1..itopk (%d)", k, itopk);
     if (max_iters < 0) return fail(ANN_EINVAL, "ann_search: max_iters = %d", max_iters);
+    if (route_given && h->d.entry_mode != ANN_ENTRY_ROUTED)
+        return fail(ANN_EINVAL, "ann_search_routed: the index does not use routed entries");
     Plan plan;
     const int rc = make_plan(h, itopk, width, &plan, "ann_search");
     if (rc != ANN_OK) return rc;
     if (nq == 0) return ANN_OK;
-    if (!queries || !out_ids || !out_dists) return fail(ANN_EINVAL, "ann_search: null argument");
+    if (!queries || !out_ids || !out_dists || (route_given && !route)) return fail(ANN_EINVAL, "ann_search: null argument");
     if (!aligned16(queries)) return fail(ANN_EINVAL, "ann_search: queries not 16-byte aligned");
-    hipStream_t stream = static_cast<hipStream_t>(stream_);
 
-    int32_t* route = nullptr;
-    if (h->d.entry_mode == ANN_ENTRY_ROUTED) {
-        const hipError_t e = hipMallocAsync(reinterpret_cast<void**>(&route), sizeof(int32_t) * (size_t)nq * h->d.route_c, stream);
+    int32_t* scratch = nullptr;
+    if (h->d.entry_mode == ANN_ENTRY_ROUTED && !route_given) {
+        const hipError_t e = hipMallocAsync(reinterpret_cast<void**>(&scratch), sizeof(int32_t) * (size_t)nq * h->d.route_c, stream);
         if (e != hipSuccess) return fail(ANN_ENOMEM, "ann_search: scratch allocation failed: %s", hipGetErrorString(e));
-        const int r = ann_route(h, queries, nq, route, stream);
+        const int r = ann_route(h, queries, nq, scratch, stream);
         if (r != ANN_OK) {
-            (void)hipFreeAsync(route, stream);
+            (void)hipFreeAsync(scratch, stream);
             return r;
         }
+        route = scratch;
     }
 
     int result = ANN_OK;
@@ -246,8 +251,24 @@ extern "C" int ann_search_counters(ann_index_t* h, const void* queries, int64_t 
             break;
         }
     }
-    if (route) (void)hipFreeAsync(route, stream);
+    if (scratch) (void)hipFreeAsync(scratch, stream);
     return result;
+}
+
+}  // namespace
+
+extern "C" int ann_search_counters(ann_index_t* h, const void* queries, int64_t nq, int k, int itopk, int width,
+                                   int max_iters, int32_t* out_ids, void* out_dists, int32_t* out_counters,
+                                   void* stream) {
+    return search_impl(h, queries, nq, nullptr, false, k, itopk, width, max_iters, out_ids, out_dists, out_counters,
+                       static_cast<hipStream_t>(stream));
+}
+
+extern "C" int ann_search_routed(ann_index_t* h, const void* queries, int64_t nq, const int32_t* routes, int k,
+                                 int itopk, int width, int max_iters, int32_t* out_ids, void* out_dists,
+                                 int32_t* out_counters, void* stream) {
+    return search_impl(h, queries, nq, routes, true, k, itopk, width, max_iters, out_ids, out_dists, out_counters,
+                       static_cast<hipStream_t>(stream));
 }
 
 extern "C" int ann_search(ann_index_t* h, const void* queries, int64_t nq, int k, int itopk, int width, int max_iters,
