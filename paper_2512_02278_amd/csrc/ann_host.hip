@@ -47,6 +47,9 @@ static int elem_size(int dtype) { return dtype == ANN_U8 ? 1 : dtype == ANN_F16 
 constexpr uint32_t kMagic = 0x414e4e31u;  // "ANN1"
 constexpr int kMaxItopk = 512, kMaxBatch = 512, kMaxWidth = 64;
 constexpr int64_t kMaxQueriesPerLaunch = 1 << 22;
+// Visited bitmap over the routed clusters: 8192 ids cover a cluster of the 100M / 16384
+// partition (about 6100 ids) with room to spare; ids beyond it use the hash.
+constexpr int kDefaultWindowBits = 8192, kMaxWindowBits = 1 << 17;
 
 }  // namespace ann
 
@@ -55,7 +58,8 @@ struct ann_index {
     ann_index_desc_t d;
     int row_bytes;
     const ann::RowVariant* variant;
-    int hash_bits_bias;  // ANN_HASH_BITS_BIAS: extra (or fewer) bits for the visited table, for tuning
+    int hash_bits_bias;  // ANN_HASH_BITS_BIAS: extra (or fewer) bits for the visited hash, for tuning
+    int window_bits;     // ANN_WINDOW_BITS: size of the visited bitmap over the routed clusters' ids
 };
 
 using namespace ann;
@@ -107,6 +111,11 @@ extern "C" int ann_index_load(const ann_index_desc_t* desc, ann_index_t** out_ha
     h->variant = best;
     const char* bias = getenv("ANN_HASH_BITS_BIAS");
     h->hash_bits_bias = bias ? atoi(bias) : 0;
+    const char* wb = getenv("ANN_WINDOW_BITS");
+    int window_bits = wb ? atoi(wb) : kDefaultWindowBits;
+    if (window_bits < 0) window_bits = 0;
+    if (window_bits > kMaxWindowBits) window_bits = kMaxWindowBits;
+    h->window_bits = d.entry_mode == ANN_ENTRY_ROUTED ? (window_bits + 31) / 32 * 32 : 0;
     *out_handle = h;
     return ANN_OK;
 }
@@ -145,11 +154,11 @@ int make_plan(const ann_index* h, int itopk, int width, Plan* plan, const char* 
     // round adds <= need, so 3/4 of its size must cover itopk + need
     int bits = 6;
     while (((3 << bits) >> 2) < itopk + need) ++bits;
-    bits += 1 + h->hash_bits_bias;  // default: one more bit, so that resets are rare
+    bits += (h->window_bits ? 0 : 1) + h->hash_bits_bias;  // without a bitmap: one more bit, so that resets are rarer
     while (((3 << bits) >> 2) < itopk + need) ++bits;
     if (bits > 13) bits = 13;
     plan->hash_bits = bits;
-    plan->lds_bytes = sizeof(uint32_t) * ((size_t(1) << bits) + 3 * (size_t)plan->cap + 64);
+    plan->lds_bytes = sizeof(uint32_t) * ((size_t(1) << bits) + 3 * (size_t)plan->cap + 64 + 32 + (size_t)h->window_bits / 32);
     return ANN_OK;
 }
 
@@ -241,6 +250,7 @@ int search_impl(ann_index_t* h, const void* queries, int64_t nq, const int32_t* 
         p.cluster_offsets = h->d.cluster_offsets;
         p.route_c = h->d.route_c;
         p.hash_bits = plan.hash_bits;
+        p.window_bits = h->window_bits;
         p.cap = plan.cap;
         p.out_ids = out_ids;
         p.out_dists = static_cast<uint32_t*>(out_dists);

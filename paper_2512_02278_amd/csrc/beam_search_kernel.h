@@ -4,12 +4,16 @@
 //   * candidate list: 64*LPL packed keys in registers, ascending, blocked layout
 //     (wave.h).  A packed key is (ordered key << 32) | (id << 1) | expanded, so one
 //     unsigned 64-bit compare orders by (key, id) and the expanded mark rides along.
-//   * visited table: open-addressing hash of ids in LDS.  It is emptied when it
-//     fills up and the ids of the current list are put back.  Forgetting other
-//     nodes cannot change the result: the list always holds the itopk best of all
-//     nodes scored so far and its worst key never rises, so a forgotten node that
-//     is scored again is rejected again; list members are always in the table and
-//     are never scored twice.  Only the number of rows gathered grows.
+//   * visited set in LDS, two parts.  (a) An exact bitmap over the id ranges of
+//     the clusters the query was routed to ("windows"): a K-means partition is
+//     stored as contiguous ids, and nearly every node a query scores lies in its
+//     routed clusters, so one bit per id of those ranges remembers them all.
+//     (b) An open-addressing hash of ids for everything outside the windows.  It
+//     is emptied when it fills up and the list's ids are put back.  Forgetting
+//     other nodes cannot change the result: the list always holds the itopk best
+//     of all nodes scored so far and its worst key never rises, so a forgotten
+//     node that is scored again is rejected again; list members are always in the
+//     visited set and are never scored twice.  Only the rows gathered grow.
 //   * per round: parent ids, surviving neighbour ids and their packed keys in LDS.
 //
 // One round (Fantasy Sec. 3.2, stage 3: beam width w, out-degree d_g):
@@ -39,7 +43,8 @@ struct SearchParams {
     const int32_t* route;            // nq * route_c nearest clusters (routed mode)
     const int64_t* cluster_offsets;  // routed mode
     int32_t route_c;
-    int32_t hash_bits;  // visited table has 1 << hash_bits slots
+    int32_t hash_bits;    // visited hash has 1 << hash_bits slots
+    int32_t window_bits;  // bits of the visited bitmap (multiple of 32; 0 = none)
     int32_t cap;        // most candidates one round can produce, multiple of 64
     int32_t* out_ids;
     uint32_t* out_dists;
@@ -59,8 +64,8 @@ __device__ __forceinline__ uint64_t splitmix64_at(uint64_t seed, uint64_t counte
     return z;
 }
 
-// True if `id` was not in the table (and now is).  The table is never full.
-__device__ __forceinline__ bool visited_insert(uint32_t* table, int hash_bits, uint32_t id) {
+// True if `id` was not in the hash (and now is).  The hash is never full.
+__device__ __forceinline__ bool hash_insert(uint32_t* table, int hash_bits, uint32_t id) {
     const uint32_t mask = (1u << hash_bits) - 1u;
     uint32_t h = (id * 0x9E3779B1u) >> (32 - hash_bits);
     for (;;) {
@@ -87,9 +92,12 @@ struct BeamSearch {
     uint64_t* ckey;
     uint32_t* cid;
     uint32_t* parents;
+    uint32_t* wtab;    // per window: first id, ids covered, first bit
+    uint32_t* bitmap;  // window_bits / 32 words
     Row row;
     uint64_t L[LPL];
-    int n_table;  // ids in the visited table
+    int n_windows;
+    int n_table;  // ids in the visited hash
     int n_dist, n_parents, n_resets;
 
     __device__ __forceinline__ BeamSearch(const SearchParams& p_, uint32_t* lds, int lane_) : p(p_), lane(lane_) {
@@ -97,7 +105,9 @@ struct BeamSearch {
         ckey = reinterpret_cast<uint64_t*>(lds + (1 << p.hash_bits));
         cid = lds + (1 << p.hash_bits) + 2 * p.cap;
         parents = cid + p.cap;
-        n_table = n_dist = n_parents = n_resets = 0;
+        wtab = parents + 64;
+        bitmap = wtab + 32;
+        n_windows = n_table = n_dist = n_parents = n_resets = 0;
     }
 
     __device__ __forceinline__ void clear_table() {
@@ -105,25 +115,47 @@ struct BeamSearch {
         n_table = 0;
     }
 
-    // Empties the table and puts the list's ids back.
+    // Bit of `id` in the visited bitmap, or -1 if no window covers it.
+    __device__ __forceinline__ int window_bit(uint32_t id) const {
+        int bit = -1;
+        for (int w = 0; w < n_windows; ++w) {
+            const uint32_t rel = id - wtab[3 * w];
+            if (rel < wtab[3 * w + 1]) bit = (int)(wtab[3 * w + 2] + rel);
+        }
+        return bit;
+    }
+
+    // 0: seen before; 1: new, remembered in the bitmap; 2: new, remembered in the hash.
+    __device__ __forceinline__ int visited_insert(uint32_t id) {
+        const int bit = window_bit(id);
+        if (bit >= 0) {
+            const uint32_t m = 1u << (bit & 31);
+            return (atomicOr(&bitmap[bit >> 5], m) & m) ? 0 : 1;
+        }
+        return hash_insert(table, p.hash_bits, id) ? 2 : 0;
+    }
+
+    // Empties the hash and puts back the list's ids that no window covers.
     __device__ __forceinline__ void reset_table() {
         clear_table();
         lds_sync();
 #pragma unroll
         for (int r = 0; r < LPL; ++r) {
-            const bool have = L[r] != kInfKey;
-            if (have) visited_insert(table, p.hash_bits, (uint32_t)L[r] >> 1);
-            n_table += __builtin_popcountll(__ballot(have));
+            const uint32_t id = (uint32_t)L[r] >> 1;
+            const bool put = L[r] != kInfKey && window_bit(id) < 0;
+            if (put) hash_insert(table, p.hash_bits, id);
+            n_table += __builtin_popcountll(__ballot(put));
         }
         ++n_resets;
     }
 
-    // Candidate ids held one per lane and round t: keep the unseen ones, packed into cid[0..m).
+    // Candidate ids held one per lane: keep the unseen ones, packed into cid[0..m).
     __device__ __forceinline__ void filter_into(int32_t id, bool valid, int& m) {
-        const bool ok = valid && id >= 0 && (int64_t)id < p.n && visited_insert(table, p.hash_bits, (uint32_t)id);
-        const uint64_t b = __ballot(ok);
-        if (ok) cid[m + rank_below(b)] = (uint32_t)id;
+        const int how = (valid && id >= 0 && (int64_t)id < p.n) ? visited_insert((uint32_t)id) : 0;
+        const uint64_t b = __ballot(how != 0);
+        if (how != 0) cid[m + rank_below(b)] = (uint32_t)id;
         m += __builtin_popcountll(b);
+        n_table += __builtin_popcountll(__ballot(how == 2));
     }
 
     // Gathers rows cid[0..m) and writes their packed keys to ckey[0..m).
@@ -190,9 +222,27 @@ struct BeamSearch {
 #pragma unroll
         for (int r = 0; r < LPL; ++r) L[r] = kInfKey;
         clear_table();
+        for (int i = lane; i < (p.window_bits >> 5); i += 64) bitmap[i] = 0u;
+        if (p.entry_mode == 1 && p.window_bits > 0) {
+            // one window per routed cluster, in routing order, until the bitmap is used up
+            uint32_t bit = 0;
+            for (int w = 0; w < p.route_c; ++w) {
+                const int32_t c = p.route[qi * p.route_c + w];
+                const int64_t lo = p.cluster_offsets[c], hi = p.cluster_offsets[c + 1];
+                const uint32_t room = (uint32_t)p.window_bits - bit;
+                const uint32_t size = (uint64_t)(hi - lo) < room ? (uint32_t)(hi - lo) : room;
+                if (lane == 0) {
+                    wtab[3 * w] = (uint32_t)lo;
+                    wtab[3 * w + 1] = size;
+                    wtab[3 * w + 2] = bit;
+                }
+                bit += size;
+            }
+            n_windows = p.route_c;
+        }
         lds_sync();
 
-        // entries (duplicates collapse in the visited table)
+        // entries (duplicates collapse in the visited set)
         int m = 0;
 #pragma unroll
         for (int t = 0; t < CPL; ++t) {
@@ -211,7 +261,6 @@ struct BeamSearch {
             }
             filter_into(e, valid, m);
         }
-        n_table += m;
         lds_sync();
         score(m);
         lds_sync();
@@ -261,7 +310,6 @@ struct BeamSearch {
             m = 0;
 #pragma unroll
             for (int t = 0; t < CPL; ++t) filter_into(nb[t], t * 64 + lane < nref, m);
-            n_table += m;
             lds_sync();
             score(m);
             lds_sync();

@@ -193,17 +193,35 @@ def test_uint8_dims_and_padded_rows(oracle, torch_cuda, dim):
     check_exact(oracle, torch_cuda, x, g, q, 10, 64, 2, 40, n_entry=8, seed=1)
 
 
-def test_small_visited_table_forces_resets(oracle, torch_cuda, monkeypatch):
-    """With the smallest table the kernel forgets visited nodes every few rounds; the
-    result must not change, only more rows are gathered."""
+def test_small_visited_hash_forces_resets(oracle, torch_cuda, monkeypatch):
+    """Without the bitmap and with the smallest hash the kernel forgets visited nodes every
+    few rounds; the result must not change, only more rows are gathered."""
     rng = np.random.default_rng(77)
     x, cen, off = clustered(rng, 8000, 128, "u8", n_centres=4)
     g = knn_graph(x, 32)
     q = queries_near(rng, x, 200, "u8")
     monkeypatch.setenv("ANN_HASH_BITS_BIAS", "-1")
+    monkeypatch.setenv("ANN_WINDOW_BITS", "0")
     gc, oc = check_exact(oracle, torch_cuda, x, g, q, 10, 128, 4, 100, n_entry=32, seed=2, entry_mode=1,
                          centroids=cen, offsets=off, route_c=1)
     assert gc[:, 3].max() >= 1 and (gc[:, 1] > oc["n_dist"]).any()
+
+
+@pytest.mark.parametrize("window_bits,route_c", [(8192, 1), (8192, 3), (512, 2), (96, 1)])
+def test_visited_bitmap_windows(oracle, torch_cuda, monkeypatch, window_bits, route_c):
+    """The visited bitmap covers the routed clusters' id ranges; ids beyond it (other
+    clusters, or a bitmap shorter than the clusters) go to the hash.  Whole, partial
+    and tiny bitmaps give the oracle's answer; a bitmap that covers the query's
+    cluster gathers no row twice."""
+    rng = np.random.default_rng(78)
+    x, cen, off = clustered(rng, 8000, 128, "u8", n_centres=4, spread=40.0)  # clusters overlap: edges cross
+    g = knn_graph(x, 32)
+    q = queries_near(rng, x, 200, "u8")
+    monkeypatch.setenv("ANN_WINDOW_BITS", str(window_bits))
+    gc, oc = check_exact(oracle, torch_cuda, x, g, q, 10, 128, 4, 100, n_entry=32, seed=2, entry_mode=1,
+                         centroids=cen, offsets=off, route_c=route_c)
+    if window_bits == 8192 and route_c == 3:
+        assert (gc[:, 1] - oc["n_dist"]).mean() < 0.05 * oc["n_dist"].mean()
 
 
 def test_edge_cases(oracle, torch_cuda):
