@@ -78,8 +78,11 @@ typedef struct {
 
 /*
  * Validates `desc`, chooses the kernel variant and returns a handle.
- * No device memory is copied or allocated.  Must be called with the device that
- * owns the arrays current.  Errors: ANN_EINVAL, ANN_EUNSUPPORTED, ANN_ENOMEM.
+ * The borrowed arrays are not copied.  For a routed uint8 index of 128 dimensions a
+ * small device array (one int32 per cluster) is allocated and filled on the default
+ * stream, which is synchronised before returning; nothing else touches the device.
+ * Must be called with the device that owns the arrays current.
+ * Errors: ANN_EINVAL, ANN_EUNSUPPORTED, ANN_ENOMEM, ANN_EHIP.
  */
 int ann_index_load(const ann_index_desc_t* desc, ann_index_t** out_handle);
 
@@ -128,7 +131,7 @@ int ann_search_routed(ann_index_t* handle, const void* queries, int64_t nq, cons
                       int width, int max_iters, int32_t* out_ids, void* out_dists, int32_t* out_counters,
                       void* stream);
 
-/* Releases the handle (host memory only).  NULL is accepted. */
+/* Releases the handle and what it owns (never the borrowed arrays).  NULL is accepted. */
 int ann_free(ann_index_t* handle);
 
 /* Text of the calling thread's last error; never NULL. */

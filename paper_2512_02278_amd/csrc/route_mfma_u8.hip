@@ -1,0 +1,184 @@
+// Routing for uint8 vectors of 128 dimensions on the matrix cores.
+//
+// Stage 1 of Fantasy (Sec. 3.2, "Local K-means Assignment") is the one dense
+// contraction on the path: Q (b x d) against the centroids C (d x C), then the
+// nearest clusters per query.  Here: shift both operands by -128 so that they fit
+// int8 (squared L2 does not change; for the inner product the shift only adds a
+// per-centroid and a per-query term), multiply on v_mfma_i32_32x32x32_i8 with exact
+// int32 accumulation, and rank by
+//     L2:  bias_c - 2 q'.c'   with bias_c = sum c'^2          (= key - sum q'^2)
+//     IP:  bias_c -   q'.c'   with bias_c = -128 sum c'       (= key + per-query terms)
+// which orders a query's centroids exactly as (key, cluster index) does.
+//
+// Tiling.  A = 32 centroids x 32 bytes, B = 32 queries x 32 bytes per instruction;
+// a wavefront keeps 64 queries (two B sets) in registers for the whole kernel and
+// walks all centroids, 32 at a time.  In the 32x32 result a lane holds 16 centroids
+// of ONE query (column = lane % 32), so the running best list of a query lives in
+// two lanes' registers and needs no exchange until the end.  Rows are visited in
+// ascending cluster order, so a strict "<" keeps the lower index among equal keys.
+#include <hip/hip_runtime.h>
+
+#include "route_mfma_u8.h"
+
+namespace ann {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+
+constexpr int kPadBias = 0x3fffffff;  // bias of the padding rows: never among the best
+
+template <int METRIC>
+__global__ void __launch_bounds__(256) centroid_bias_kernel(const uint8_t* centroids, int n_clusters, int padded,
+                                                            int32_t* bias) {
+    const int c = blockIdx.x * 256 + threadIdx.x;
+    if (c >= padded) return;
+    if (c >= n_clusters) {
+        bias[c] = kPadBias;
+        return;
+    }
+    const uint32_t* row = reinterpret_cast<const uint32_t*>(centroids + (int64_t)c * 128);
+    int32_t acc = 0;
+    for (int i = 0; i < 32; ++i) {
+        const uint32_t w = row[i] ^ 0x80808080u;
+        if (METRIC == 0)
+            acc = __builtin_amdgcn_sdot4((int)w, (int)w, acc, false);
+        else
+            acc = __builtin_amdgcn_sdot4((int)w, 0x01010101, acc, false);
+    }
+    bias[c] = METRIC == 0 ? acc : -128 * acc;
+}
+
+template <int METRIC, int RC>
+__global__ void __launch_bounds__(256) route_mfma_u8_kernel(const uint8_t* __restrict__ centroids,
+                                                            const int32_t* __restrict__ bias, int n_clusters,
+                                                            const uint8_t* __restrict__ queries, int64_t nq,
+                                                            int32_t* __restrict__ out) {
+    constexpr int NQS = 2;  // query sets of 32 per wavefront
+    __shared__ uint64_t pool[4][NQS * 32][2][RC];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int col = lane & 31, half = lane >> 5;
+    const int64_t q0 = ((int64_t)blockIdx.x * 4 + wave) * (NQS * 32);
+    if (q0 >= nq) return;  // whole wavefront; no block-wide barrier is used below
+
+    // B: lane holds, for query (q0 + 32 s + col), the 16 bytes number 2 t + half of the row
+    v4i b[NQS][4];
+#pragma unroll
+    for (int s = 0; s < NQS; ++s) {
+        int64_t q = q0 + s * 32 + col;
+        if (q >= nq) q = nq - 1;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            b[s][t] = *reinterpret_cast<const v4i*>(queries + q * 128 + (2 * t + half) * 16);
+            b[s][t] ^= (int)0x80808080;
+        }
+    }
+    int32_t best_s[NQS][RC], best_i[NQS][RC];
+#pragma unroll
+    for (int s = 0; s < NQS; ++s)
+#pragma unroll
+        for (int r = 0; r < RC; ++r) {
+            best_s[s][r] = 0x7fffffff;
+            best_i[s][r] = 0x7fffffff;
+        }
+
+    const int n_tiles = (n_clusters + 31) / 32;
+    for (int ct = 0; ct < n_tiles; ++ct) {
+        int arow = ct * 32 + col;
+        if (arow >= n_clusters) arow = n_clusters - 1;
+        v4i a[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            a[t] = *reinterpret_cast<const v4i*>(centroids + (int64_t)arow * 128 + (2 * t + half) * 16);
+            a[t] ^= (int)0x80808080;
+        }
+        // result element v of a lane is row 8 (v / 4) + 4 half + v % 4 of the tile
+        v4i bs[4];
+#pragma unroll
+        for (int g = 0; g < 4; ++g) bs[g] = *reinterpret_cast<const v4i*>(bias + ct * 32 + 8 * g + 4 * half);
+#pragma unroll
+        for (int s = 0; s < NQS; ++s) {
+            v16i acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+            for (int t = 0; t < 4; ++t) acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[t], b[s][t], acc, 0, 0, 0);
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int32_t score = bs[v / 4][v % 4] - (METRIC == 0 ? 2 : 1) * acc[v];
+                const int32_t idx = ct * 32 + 8 * (v / 4) + 4 * half + (v % 4);
+                if (score < best_s[s][RC - 1]) {
+                    // insertion; equal scores stay behind the earlier (smaller) index
+                    int32_t cs = score, ci = idx;
+#pragma unroll
+                    for (int r = 0; r < RC; ++r) {
+                        const bool first = cs < best_s[s][r];
+                        const int32_t ts = best_s[s][r], ti = best_i[s][r];
+                        best_s[s][r] = first ? cs : ts;
+                        best_i[s][r] = first ? ci : ti;
+                        cs = first ? ts : cs;
+                        ci = first ? ti : ci;
+                    }
+                }
+            }
+        }
+    }
+
+    // the two lanes of a query merge their ascending lists through LDS
+#pragma unroll
+    for (int s = 0; s < NQS; ++s)
+#pragma unroll
+        for (int r = 0; r < RC; ++r)
+            pool[wave][s * 32 + col][half][r] =
+                ((uint64_t)((uint32_t)best_s[s][r] ^ 0x80000000u) << 32) | (uint32_t)best_i[s][r];
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    // lane -> query (q0 + lane): every lane merges one query
+    const int64_t q = q0 + lane;
+    if (q < nq) {
+        int ia = 0, ib = 0;
+        for (int r = 0; r < RC; ++r) {
+            const uint64_t x = ia < RC ? pool[wave][lane][0][ia] : ~0ull;
+            const uint64_t y = ib < RC ? pool[wave][lane][1][ib] : ~0ull;
+            const bool take_x = x < y;
+            out[q * RC + r] = (int32_t)(uint32_t)(take_x ? x : y);
+            ia += take_x ? 1 : 0;
+            ib += take_x ? 0 : 1;
+        }
+    }
+}
+
+template <int METRIC>
+static hipError_t launch_rc(int rc, const uint8_t* centroids, const int32_t* bias, int n_clusters,
+                            const uint8_t* queries, int64_t nq, int32_t* out, hipStream_t stream) {
+    const dim3 grid((unsigned)((nq + 255) / 256)), block(256);
+    switch (rc) {
+        case 1: hipLaunchKernelGGL((route_mfma_u8_kernel<METRIC, 1>), grid, block, 0, stream, centroids, bias, n_clusters, queries, nq, out); break;
+        case 2: hipLaunchKernelGGL((route_mfma_u8_kernel<METRIC, 2>), grid, block, 0, stream, centroids, bias, n_clusters, queries, nq, out); break;
+        case 3: hipLaunchKernelGGL((route_mfma_u8_kernel<METRIC, 3>), grid, block, 0, stream, centroids, bias, n_clusters, queries, nq, out); break;
+        case 4: hipLaunchKernelGGL((route_mfma_u8_kernel<METRIC, 4>), grid, block, 0, stream, centroids, bias, n_clusters, queries, nq, out); break;
+        case 5: hipLaunchKernelGGL((route_mfma_u8_kernel<METRIC, 5>), grid, block, 0, stream, centroids, bias, n_clusters, queries, nq, out); break;
+        case 6: hipLaunchKernelGGL((route_mfma_u8_kernel<METRIC, 6>), grid, block, 0, stream, centroids, bias, n_clusters, queries, nq, out); break;
+        case 7: hipLaunchKernelGGL((route_mfma_u8_kernel<METRIC, 7>), grid, block, 0, stream, centroids, bias, n_clusters, queries, nq, out); break;
+        case 8: hipLaunchKernelGGL((route_mfma_u8_kernel<METRIC, 8>), grid, block, 0, stream, centroids, bias, n_clusters, queries, nq, out); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_centroid_bias_u8(int metric, const uint8_t* centroids, int n_clusters, int32_t* bias,
+                                   hipStream_t stream) {
+    const int padded = route_mfma_u8_padded(n_clusters);
+    const dim3 grid((unsigned)((padded + 255) / 256)), block(256);
+    if (metric == 0)
+        hipLaunchKernelGGL((centroid_bias_kernel<0>), grid, block, 0, stream, centroids, n_clusters, padded, bias);
+    else
+        hipLaunchKernelGGL((centroid_bias_kernel<1>), grid, block, 0, stream, centroids, n_clusters, padded, bias);
+    return hipGetLastError();
+}
+
+hipError_t launch_route_mfma_u8(int metric, int route_c, const uint8_t* centroids, const int32_t* bias, int n_clusters,
+                                const uint8_t* queries, int64_t nq, int32_t* out, hipStream_t stream) {
+    return metric == 0 ? launch_rc<0>(route_c, centroids, bias, n_clusters, queries, nq, out, stream)
+                       : launch_rc<1>(route_c, centroids, bias, n_clusters, queries, nq, out, stream);
+}
+
+}  // namespace ann

@@ -260,6 +260,35 @@ def test_float_parity(oracle, torch_cuda, dt, dim, metric, itopk, width, degree,
     print(f"{dt} dim={dim} metric={metric}: {same:.3f} of the queries have identical id lists")
 
 
+@pytest.mark.parametrize("metric", [0, 1])
+@pytest.mark.parametrize("n_clusters,route_c,nq", [(300, 4, 100), (32, 1, 1), (1000, 8, 777), (5, 5, 64), (4097, 3, 300)])
+def test_uint8_matrix_core_routing_is_exact(oracle, torch_cuda, monkeypatch, metric, n_clusters, route_c, nq):
+    """uint8 d=128 routing runs on the matrix cores (shifted to int8, exact int32 sums) and must give
+    the oracle's clusters in the oracle's order, ties by cluster index included; the plain kernel
+    (matrix cores switched off) must give the same."""
+    from paper_2512_02278_amd import ann
+
+    torch = torch_cuda
+    rng = np.random.default_rng(n_clusters + metric)
+    cen = rng.integers(0, 256, (n_clusters, 128), dtype=np.uint8)
+    cen[rng.integers(0, n_clusters, n_clusters // 3)] = cen[0]           # equal centroids: equal keys
+    cen[:, :] = np.where(rng.random(cen.shape) < 0.1, rng.choice([0, 255], cen.shape), cen)  # extremes of the range
+    q = rng.integers(0, 256, (nq, 128), dtype=np.uint8)
+    q[: nq // 4] = cen[rng.integers(0, n_clusters, nq // 4)]
+    want = oracle.route(cen, q, route_c, metric)
+    xt = torch.zeros((64, 128), dtype=torch.uint8, device="cuda")
+    gt = torch.zeros((64, 4), dtype=torch.int32, device="cuda")
+    off = torch.zeros(n_clusters + 1, dtype=torch.int64, device="cuda")
+    for no_mfma in (False, True):
+        if no_mfma:
+            monkeypatch.setenv("ANN_NO_MFMA_ROUTE", "1")
+        h = ann.ann_index_load(xt, gt, metric=metric, entry_mode=1, centroids=torch.from_numpy(cen).cuda(),
+                               cluster_offsets=off, route_c=route_c)
+        got = ann.ann_route(h, torch.from_numpy(q).cuda()).cpu().numpy()
+        ann.ann_free(h)
+        assert np.array_equal(got, want), (no_mfma, np.argwhere(got != want)[:5].tolist())
+
+
 def test_route_matches_oracle(oracle, torch_cuda):
     from paper_2512_02278_amd import ann
 
