@@ -205,6 +205,14 @@ def main() -> int:
 
     ann.ann_free(h)
 
+    # a plain copy of known size (1 GiB read, 1 GiB written): calibrates profiler byte counters
+    src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).random_(0, 256)
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        ann.ann_calibration_copy(dst, src)
+    torch.cuda.synchronize()
+    del src, dst
+
     # ------------------------------------------------------------------ roofline of the dominant kernel
     if algo["n_dist"] is not None:
         algo_bq = metrics.algorithmic_bytes_per_query(algo["n_dist"], algo["n_parents"], row_bytes, degree, row_bytes, k)

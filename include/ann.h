@@ -141,6 +141,14 @@ const char* ann_last_error(void);
  * negative error code; lets callers reason about occupancy. */
 int64_t ann_lds_bytes(ann_index_t* handle, int itopk, int width);
 
+/*
+ * Measurement aid, not part of the search: copies `bytes` (a multiple of 16, both
+ * pointers DEVICE and 16-byte aligned) with a plain grid-stride kernel named
+ * ann_calibration_copy_kernel.  A profiler's HBM byte counters can be calibrated
+ * against this transfer of known size (bytes read + bytes written).
+ */
+int ann_calibration_copy(void* dst, const void* src, int64_t bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -22,7 +22,7 @@ ANN_OK, ANN_EINVAL, ANN_EUNSUPPORTED, ANN_ENOMEM, ANN_EHIP = 0, -1, -2, -3, -4
 _DTYPES = {torch.uint8: ANN_U8, torch.float16: ANN_F16, torch.float32: ANN_F32}
 
 EXPORTS = ("ann_index_load", "ann_search", "ann_search_counters", "ann_search_routed", "ann_route", "ann_free",
-           "ann_last_error", "ann_lds_bytes")
+           "ann_last_error", "ann_lds_bytes", "ann_calibration_copy")
 
 
 class ann_index_desc_t(ctypes.Structure):
@@ -66,6 +66,8 @@ def lib() -> ctypes.CDLL:
         L.ann_free.restype = ctypes.c_int
         L.ann_last_error.argtypes = []
         L.ann_last_error.restype = ctypes.c_char_p
+        L.ann_calibration_copy.argtypes = [vp, vp, i64, vp]
+        L.ann_calibration_copy.restype = ctypes.c_int
         L.ann_lds_bytes.argtypes = [vp, i32, i32]
         L.ann_lds_bytes.restype = ctypes.c_int64
         _lib = L
@@ -191,3 +193,11 @@ def ann_free(h: Handle) -> None:
         _check(lib().ann_free(h.ptr))
         h.ptr = None
         h._keep = None
+
+
+def ann_calibration_copy(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None:
+    """Plain copy kernel of known size, for calibrating a profiler's byte counters."""
+    nbytes = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() != nbytes or not (dst.is_contiguous() and src.is_contiguous()):
+        raise ValueError("dst and src must be contiguous and of equal size")
+    _check(lib().ann_calibration_copy(_dev_ptr(dst, "dst"), _dev_ptr(src, "src"), nbytes, _stream(stream)))

@@ -311,3 +311,20 @@ extern "C" int ann_search(ann_index_t* h, const void* queries, int64_t nq, int k
                           int32_t* out_ids, void* out_dists, void* stream) {
     return ann_search_counters(h, queries, nq, k, itopk, width, max_iters, out_ids, out_dists, nullptr, stream);
 }
+
+namespace ann {
+__global__ void __launch_bounds__(256) ann_calibration_copy_kernel(uint4* __restrict__ dst, const uint4* __restrict__ src,
+                                                                   int64_t n16) {
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (int64_t)gridDim.x * 256) dst[i] = src[i];
+}
+}  // namespace ann
+
+extern "C" int ann_calibration_copy(void* dst, const void* src, int64_t bytes, void* stream) {
+    if (!dst || !src || bytes < 0 || bytes % 16 != 0 || !aligned16(dst) || !aligned16(src))
+        return fail(ANN_EINVAL, "ann_calibration_copy: pointers must be non-null and 16-byte aligned, bytes a multiple of 16");
+    if (bytes == 0) return ANN_OK;
+    hipLaunchKernelGGL(ann::ann_calibration_copy_kernel, dim3(256 * 16), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       static_cast<uint4*>(dst), static_cast<const uint4*>(src), bytes / 16);
+    const hipError_t e = hipGetLastError();
+    return e == hipSuccess ? ANN_OK : fail(ANN_EHIP, "ann_calibration_copy: launch failed: %s", hipGetErrorString(e));
+}
