@@ -99,10 +99,15 @@ extern "C" int ann_index_load(const ann_index_desc_t* desc, ann_index_t** out_ha
         if (d.route_c < 1 || d.route_c > d.n_clusters || d.route_c > kMaxRouteC)
             return fail(ANN_EINVAL, "ann_index_load: route_c = %d outside 1..min(n_clusters, %d)", d.route_c, kMaxRouteC);
     }
+    // the smallest variant that covers the row; among equals the one with fewer lanes per row
+    // (more rows per instruction).  ANN_ROW_LANES pins the lanes per row, for tuning.
+    const char* pin = getenv("ANN_ROW_LANES");
+    const int pin_g = pin ? atoi(pin) : 0;
     const RowVariant* best = nullptr;
     for (const RowVariant& v : kRowVariants)
         if (v.dtype == d.dtype && v.metric == d.metric && (int64_t)v.g * v.nch * 16 >= row_bytes &&
-            (!best || v.g * v.nch < best->g * best->nch))
+            (pin_g == 0 || v.g == pin_g) &&
+            (!best || v.g * v.nch < best->g * best->nch || (v.g * v.nch == best->g * best->nch && v.g < best->g)))
             best = &v;
     if (!best) return fail(ANN_EUNSUPPORTED, "ann_index_load: no kernel variant for rows of %lld bytes of this dtype", (long long)row_bytes);
     ann_index* h = new (std::nothrow) ann_index;

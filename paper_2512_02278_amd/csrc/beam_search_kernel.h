@@ -158,9 +158,24 @@ struct BeamSearch {
         n_table += __builtin_popcountll(__ballot(how == 2));
     }
 
-    // Gathers rows cid[0..m) and writes their packed keys to ckey[0..m).
-    __device__ __forceinline__ void score(int m) {
+    // The list entry number itopk-1: a new key that is not below it cannot enter the list
+    // (the empty key while the list is not full).
+    __device__ __forceinline__ uint64_t list_worst() const {
+        const int e = p.itopk - 1;
+        uint64_t v = L[0];
+#pragma unroll
+        for (int r = 1; r < LPL; ++r) v = (e % LPL == r) ? L[r] : v;
+        const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)v, e / LPL);
+        const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(v >> 32), e / LPL);
+        return ((uint64_t)hi << 32) | lo;
+    }
+
+    // Gathers rows cid[0..m) and writes the packed keys that can enter the list to
+    // ckey[0..returned count).
+    __device__ __forceinline__ int score(int m) {
         const int grp = lane / G;
+        const uint64_t worst = list_worst();
+        int kept = 0;
         for (int j0 = 0; j0 < m; j0 += RPS * U) {
             u32x4 x[U][NCH];
             uint32_t id[U];
@@ -175,14 +190,20 @@ struct BeamSearch {
             for (int u = 0; u < U; ++u) {
                 const int j = j0 + u * RPS + grp;
                 const uint32_t okey = row.key(x[u], lane);
-                if (j < m && row.lg == 0) ckey[j] = ((uint64_t)okey << 32) | ((uint64_t)id[u] << 1);
+                const uint64_t packed = ((uint64_t)okey << 32) | ((uint64_t)id[u] << 1);
+                const bool keep = j < m && row.lg == 0 && packed < worst;
+                const uint64_t b = __ballot(keep);
+                if (keep) ckey[kept + rank_below(b)] = packed;
+                kept += __builtin_popcountll(b);
             }
         }
         n_dist += m;
+        return kept;
     }
 
-    // list <- itopk smallest of list U ckey[base .. base + 64*R), R registers per lane.
-    template <int R>
+    // list <- itopk smallest of list U ckey[base .. base + 64*R), R registers per lane;
+    // KMAX >= the number of real keys in the batch (a power of two, at most 64*R).
+    template <int R, int KMAX>
     __device__ __forceinline__ void merge_batch(int base, int m) {
         uint64_t c[R];
 #pragma unroll
@@ -190,7 +211,7 @@ struct BeamSearch {
             const int j = base + lane * R + r;
             c[r] = j < m ? ckey[j] : kInfKey;
         }
-        bitonic_sort<R>(c, lane);
+        bitonic_sort_runs<R, KMAX>(c, lane);
         lds_sync();  // all reads of this batch done before it is overwritten
 #pragma unroll
         for (int r = 0; r < R; ++r) ckey[base + lane * R + r] = c[r];
@@ -212,9 +233,13 @@ struct BeamSearch {
     __device__ __forceinline__ void merge_all(int m) {
         int base = 0;
         if constexpr (BR == 2) {
-            for (; m - base > 64; base += 128) merge_batch<2>(base, m);
+            for (; m - base > 64; base += 128) merge_batch<2, 128>(base, m);
         }
-        for (; base < m; base += 64) merge_batch<1>(base, m);
+        if (m - base > 16) {
+            for (; base < m; base += 64) merge_batch<1, 64>(base, m);
+        } else if (m - base > 0) {
+            merge_batch<1, 16>(base, m);
+        }
     }
 
     __device__ __forceinline__ void run(int64_t qi) {
@@ -262,7 +287,7 @@ struct BeamSearch {
             filter_into(e, valid, m);
         }
         lds_sync();
-        score(m);
+        m = score(m);
         lds_sync();
         merge_all(m);
 
@@ -311,7 +336,7 @@ struct BeamSearch {
 #pragma unroll
             for (int t = 0; t < CPL; ++t) filter_into(nb[t], t * 64 + lane < nref, m);
             lds_sync();
-            score(m);
+            m = score(m);
             lds_sync();
             merge_all(m);
         }

@@ -15,7 +15,7 @@ namespace ann {
 
 // X(dtype, metric, G, NCH)
 #define ANN_ROW_VARIANTS(X)                                                  \
-    X(kU8, kL2, 8, 1) X(kU8, kIP, 8, 1) X(kU8, kL2, 8, 2) X(kU8, kIP, 8, 2)   \
+    X(kU8, kL2, 8, 1) X(kU8, kIP, 8, 1) X(kU8, kL2, 8, 2) X(kU8, kIP, 8, 2) X(kU8, kL2, 4, 2) X(kU8, kIP, 4, 2) \
     X(kF16, kL2, 8, 2) X(kF16, kIP, 8, 2) X(kF16, kL2, 32, 3) X(kF16, kIP, 32, 3) \
     X(kF32, kL2, 8, 3) X(kF32, kIP, 8, 3) X(kF32, kL2, 32, 4) X(kF32, kIP, 32, 4)
 

@@ -22,26 +22,53 @@ __device__ __forceinline__ int rank_below(uint64_t mask) {
     return (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
 }
 
-// Value of `v` held by lane (lane ^ mask).
-__device__ __forceinline__ uint32_t xor_lane(uint32_t v, int lane, int mask) {
-    return (uint32_t)__builtin_amdgcn_ds_bpermute((lane ^ mask) << 2, (int)v);
+// Value of `v` held by lane (lane ^ MASK), MASK a compile-time constant.  Inside a row of 16
+// lanes the exchange is a DPP move (quad permutes, half-row and row mirrors, rotate by 8);
+// across rows it is a v_permlane16_swap / v_permlane32_swap of the register with itself,
+// after which each lane picks the half it did not own.  No LDS traffic.
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_move(uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, CTRL, 0xf, 0xf, false);
 }
-__device__ __forceinline__ uint64_t xor_lane64(uint64_t v, int lane, int mask) {
-    uint32_t lo = xor_lane((uint32_t)v, lane, mask);
-    uint32_t hi = xor_lane((uint32_t)(v >> 32), lane, mask);
+template <int MASK>
+__device__ __forceinline__ uint32_t xor_lane(uint32_t v, int lane) {
+    static_assert(MASK >= 0 && MASK < 64, "lane mask");
+    constexpr int low = MASK & 15;
+    if constexpr (low == 1) v = dpp_move<0xB1>(v);        // quad_perm [1,0,3,2]
+    else if constexpr (low == 2) v = dpp_move<0x4E>(v);   // quad_perm [2,3,0,1]
+    else if constexpr (low == 3) v = dpp_move<0x1B>(v);   // quad_perm [3,2,1,0]
+    else if constexpr (low == 4) v = dpp_move<0x1B>(dpp_move<0x141>(v));  // (i ^ 7) ^ 3
+    else if constexpr (low == 7) v = dpp_move<0x141>(v);  // row_half_mirror
+    else if constexpr (low == 8) v = dpp_move<0x128>(v);  // row_ror:8
+    else if constexpr (low == 15) v = dpp_move<0x140>(v); // row_mirror
+    else static_assert(low == 0, "unsupported lane mask");
+    if constexpr ((MASK & 16) != 0) {
+        auto r = __builtin_amdgcn_permlane16_swap(v, v, false, false);
+        v = (lane & 16) ? r[0] : r[1];
+    }
+    if constexpr ((MASK & 32) != 0) {
+        auto r = __builtin_amdgcn_permlane32_swap(v, v, false, false);
+        v = (lane & 32) ? r[0] : r[1];
+    }
+    return v;
+}
+template <int MASK>
+__device__ __forceinline__ uint64_t xor_lane64(uint64_t v, int lane) {
+    uint32_t lo = xor_lane<MASK>((uint32_t)v, lane);
+    uint32_t hi = xor_lane<MASK>((uint32_t)(v >> 32), lane);
     return ((uint64_t)hi << 32) | lo;
 }
 
 // Butterfly sum over groups of G consecutive lanes; every lane of a group ends up
 // with the same value, and the order of additions is the same for every group.
-template <int G, class T>
+template <int G, int M = 1, class T>
 __device__ __forceinline__ T group_sum(T v, int lane) {
-#pragma unroll
-    for (int m = 1; m < G; m <<= 1) {
-        uint32_t o = xor_lane(__builtin_bit_cast(uint32_t, v), lane, m);
-        v = v + __builtin_bit_cast(T, o);
+    if constexpr (M < G) {
+        const uint32_t o = xor_lane<M>(__builtin_bit_cast(uint32_t, v), lane);
+        return group_sum<G, M * 2>(v + __builtin_bit_cast(T, o), lane);
+    } else {
+        return v;
     }
-    return v;
 }
 
 __device__ __forceinline__ void order2(uint64_t& lo, uint64_t& hi) {
@@ -64,7 +91,7 @@ __device__ __forceinline__ void bitonic_clean(uint64_t (&v)[R], int lane) {
             constexpr int lm = J / R;
             const bool low = (lane & lm) == 0;
 #pragma unroll
-            for (int r = 0; r < R; ++r) v[r] = pick(v[r], xor_lane64(v[r], lane, lm), low);
+            for (int r = 0; r < R; ++r) v[r] = pick(v[r], xor_lane64<lm>(v[r], lane), low);
         } else {
 #pragma unroll
             for (int r = 0; r < R; ++r)
@@ -76,9 +103,9 @@ __device__ __forceinline__ void bitonic_clean(uint64_t (&v)[R], int lane) {
 
 // Merge step for runs of length K/2 into runs of length K: one mirror stage
 // (e against e ^ (K-1)), then half-cleaners; recurses up to the full width.
-template <int R, int K>
+template <int R, int K, int KMAX>
 __device__ __forceinline__ void bitonic_sort_from(uint64_t (&v)[R], int lane) {
-    if constexpr (K <= 64 * R) {
+    if constexpr (K <= KMAX) {
         if constexpr (K <= R) {
 #pragma unroll
             for (int r = 0; r < R; ++r)
@@ -88,19 +115,26 @@ __device__ __forceinline__ void bitonic_sort_from(uint64_t (&v)[R], int lane) {
             const bool low = (lane & (K / (2 * R))) == 0;
             uint64_t o[R];
 #pragma unroll
-            for (int r = 0; r < R; ++r) o[r] = xor_lane64(v[R - 1 - r], lane, lm);
+            for (int r = 0; r < R; ++r) o[r] = xor_lane64<lm>(v[R - 1 - r], lane);
 #pragma unroll
             for (int r = 0; r < R; ++r) v[r] = pick(v[r], o[r], low);
         }
         bitonic_clean<R, K / 4>(v, lane);
-        bitonic_sort_from<R, K * 2>(v, lane);
+        bitonic_sort_from<R, K * 2, KMAX>(v, lane);
     }
 }
 
 // Full ascending sort of 64*R blocked keys.
 template <int R>
 __device__ __forceinline__ void bitonic_sort(uint64_t (&v)[R], int lane) {
-    bitonic_sort_from<R, 2>(v, lane);
+    bitonic_sort_from<R, 2, 64 * R>(v, lane);
+}
+
+// Sorts every aligned run of KMAX keys on its own.  With real keys only among the first
+// KMAX and the empty key everywhere else, that already sorts all 64*R.
+template <int R, int KMAX>
+__device__ __forceinline__ void bitonic_sort_runs(uint64_t (&v)[R], int lane) {
+    bitonic_sort_from<R, 2, KMAX>(v, lane);
 }
 
 // Sorts 64*R blocked keys that form one bitonic run.
