@@ -3,7 +3,9 @@ from __future__ import annotations
 
 import concurrent.futures
 import glob
+import json
 import os
+import re
 import subprocess
 import sys
 
@@ -14,16 +16,42 @@ LIB = os.path.join(HERE, "libann.so")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-command-line-argument",
+         "-Rpass-analysis=kernel-resource-usage",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-I", INCLUDE, "-I", CSRC]
+
+
+EXTRA = os.environ.get("ANN_EXTRA_FLAGS", "").split()  # e.g. -DNAME=VALUE switches while tuning
+
+
+RESOURCES = {}  # kernel name -> {"VGPRs": .., "ScratchSize": .., "Occupancy": ..}, filled by _compile
+
+
+def _resources(stderr: str) -> str:
+    """Collects the compiler's per-kernel resource remarks; returns what is left of stderr."""
+    rest, name = [], None
+    for line in stderr.splitlines():
+        if "kernel-resource-usage" in line:
+            m = re.search(r"remark:\s+(.*?)\s+\[-Rpass", line)
+            if m:
+                key, _, val = m.group(1).partition(":")
+                if key.strip() == "Function Name":
+                    name = val.strip()
+                    RESOURCES[name] = {}
+                elif name:
+                    RESOURCES[name][key.strip().split(" [")[0]] = val.strip()
+            continue
+        if re.match(r"^\s*\d+ \| |^\s*\| |^In file included from|^\s+\d+ remarks? generated", line) or "packed-fp32-ops" in line:
+            continue  # source echo of the remarks; hipcc's host pass not knowing the packed-fp32 feature is harmless
+        rest.append(line)
+    return "\n".join(rest)
 
 
 def _compile(src: str) -> str:
     obj = os.path.join(OBJ, os.path.basename(src) + ".o")
-    r = subprocess.run(["hipcc", *FLAGS, "-c", src, "-o", obj], capture_output=True, text=True)
-    # hipcc's host pass does not know the packed-fp32 feature and says so; that is harmless
-    err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
+    r = subprocess.run(["hipcc", *FLAGS, *EXTRA, "-c", src, "-o", obj], capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"hipcc failed on {src}:\n{r.stderr}")
+    err = _resources(r.stderr)
     if err.strip():
         sys.stderr.write(err + "\n")
     return obj
@@ -34,6 +62,13 @@ def build(jobs: int = 8) -> str:
     srcs = sorted(glob.glob(os.path.join(CSRC, "*.hip")))
     with concurrent.futures.ThreadPoolExecutor(max_workers=jobs) as ex:
         objs = list(ex.map(_compile, srcs))
+    # a search kernel that keeps its list or query in scratch memory runs at half speed: refuse it
+    spilled = {k: v for k, v in RESOURCES.items()
+               if v.get("ScratchSize", "0") != "0" or v.get("VGPRs Spill", "0") != "0"}
+    if spilled:
+        raise RuntimeError("kernels using scratch memory: " + ", ".join(f"{k} {v}" for k, v in spilled.items()))
+    with open(os.path.join(OBJ, "resources.json"), "w") as f:
+        json.dump(RESOURCES, f, indent=1, sort_keys=True)
     subprocess.run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs], check=True)
     return LIB
 

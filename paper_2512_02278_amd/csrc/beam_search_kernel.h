@@ -162,11 +162,12 @@ struct BeamSearch {
     // (the empty key while the list is not full).
     __device__ __forceinline__ uint64_t list_worst() const {
         const int e = p.itopk - 1;
-        uint64_t v = L[0];
+        uint64_t mine = kInfKey;
 #pragma unroll
-        for (int r = 1; r < LPL; ++r) v = (e % LPL == r) ? L[r] : v;
-        const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)v, e / LPL);
-        const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(v >> 32), e / LPL);
+        for (int r = 0; r < LPL; ++r)
+            if (lane * LPL + r == e) mine = L[r];
+        const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)mine, e / LPL);
+        const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(mine >> 32), e / LPL);
         return ((uint64_t)hi << 32) | lo;
     }
 
@@ -174,7 +175,11 @@ struct BeamSearch {
     // ckey[0..returned count).
     __device__ __forceinline__ int score(int m) {
         const int grp = lane / G;
+#ifdef ANN_NO_WORST_FILTER
+        const uint64_t worst = kInfKey;
+#else
         const uint64_t worst = list_worst();
+#endif
         int kept = 0;
         for (int j0 = 0; j0 < m; j0 += RPS * U) {
             u32x4 x[U][NCH];
@@ -363,8 +368,11 @@ struct BeamSearch {
 
 // Workgroup b runs on XCD b % 8 (round-robin dispatch), so consecutive queries are
 // kept on one XCD and its L2: query = (b % 8) * q_per_xcd + b / 8.
+// The small uint8 variants are asked to fit 8 wavefronts per SIMD (64 VGPRs, 96 SGPRs): with about
+// 5 KB of LDS per query that is the 32 queries per CU the latency-bound loop wants.
 template <class Row, int LPL, int CPL>
-__global__ void __launch_bounds__(64) beam_search_kernel(const SearchParams p) {
+__global__ void __launch_bounds__(64, (Row::kDtype == kU8 && LPL <= 4 && CPL <= 2) ? 8 : 1)
+    beam_search_kernel(const SearchParams p) {
     extern __shared__ uint32_t lds[];
     const int64_t b = blockIdx.x;
     const int64_t local = (b & 7) * p.q_per_xcd + (b >> 3);

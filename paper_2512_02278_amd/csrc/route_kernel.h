@@ -25,7 +25,8 @@ struct RouteParams {
 
 template <class Row>
 __global__ void __launch_bounds__(64) route_kernel(const RouteParams p) {
-    __shared__ uint64_t pool[64];
+    constexpr int PR = (64 / Row::G * kMaxRouteC + 63) / 64;  // registers per lane of the final sort
+    __shared__ uint64_t pool[64 * PR];
     const int lane = lane_id();
     const int64_t qi = blockIdx.x;
     if (qi >= p.nq) return;
@@ -54,18 +55,22 @@ __global__ void __launch_bounds__(64) route_kernel(const RouteParams p) {
             }
         }
     }
-    // RPS groups x kMaxRouteC entries <= 64 keys: sort them in one go
-    pool[lane] = kInfKey;
+    // RPS groups x kMaxRouteC entries: sort them in one go
+#pragma unroll
+    for (int r = 0; r < PR; ++r) pool[r * 64 + lane] = kInfKey;
     __syncthreads();
     if (row.lg == 0) {
 #pragma unroll
-        for (int i = 0; i < kMaxRouteC; ++i)
-            if (grp * kMaxRouteC + i < 64) pool[grp * kMaxRouteC + i] = best[i];
+        for (int i = 0; i < kMaxRouteC; ++i) pool[grp * kMaxRouteC + i] = best[i];
     }
     __syncthreads();
-    uint64_t v[1] = {pool[lane]};
-    bitonic_sort<1>(v, lane);
-    if (lane < p.route_c) p.out[qi * p.route_c + lane] = (int32_t)(uint32_t)v[0];
+    uint64_t v[PR];
+#pragma unroll
+    for (int r = 0; r < PR; ++r) v[r] = pool[lane * PR + r];
+    bitonic_sort<PR>(v, lane);
+#pragma unroll
+    for (int r = 0; r < PR; ++r)
+        if (lane * PR + r < p.route_c) p.out[qi * p.route_c + lane * PR + r] = (int32_t)(uint32_t)v[r];
 }
 
 }  // namespace ann

@@ -30,9 +30,17 @@ template <int CTRL>
 __device__ __forceinline__ uint32_t dpp_move(uint32_t v) {
     return (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, CTRL, 0xf, 0xf, false);
 }
+#ifndef ANN_XOR_IMPL
+#define ANN_XOR_IMPL 1
+#endif
 template <int MASK>
 __device__ __forceinline__ uint32_t xor_lane(uint32_t v, int lane) {
     static_assert(MASK >= 0 && MASK < 64, "lane mask");
+#if ANN_XOR_IMPL == 0
+    return (uint32_t)__builtin_amdgcn_ds_bpermute((lane ^ MASK) << 2, (int)v);
+#elif ANN_XOR_IMPL == 2
+    if constexpr ((MASK & 48) != 0) return (uint32_t)__builtin_amdgcn_ds_bpermute((lane ^ MASK) << 2, (int)v);
+#endif
     constexpr int low = MASK & 15;
     if constexpr (low == 1) v = dpp_move<0xB1>(v);        // quad_perm [1,0,3,2]
     else if constexpr (low == 2) v = dpp_move<0x4E>(v);   // quad_perm [2,3,0,1]
