@@ -265,6 +265,7 @@ int search_impl(ann_index_t* h, const void* queries, int64_t nq, const int32_t* 
         p.row_bytes = h->row_bytes;
         p.graph = h->d.graph;
         p.degree = h->d.degree;
+        p.degree_inv = ((1u << 20) + (uint32_t)h->d.degree - 1) / (uint32_t)h->d.degree;
         p.queries = static_cast<const uint8_t*>(queries);
         p.nq = nq;
         p.q_base = q0;

@@ -25,6 +25,10 @@
 
 #include "row_ops.h"
 
+#ifndef ANN_MIN_WAVES
+#define ANN_MIN_WAVES 7
+#endif
+
 namespace ann {
 
 struct SearchParams {
@@ -34,6 +38,7 @@ struct SearchParams {
     int32_t row_bytes;
     const int32_t* graph;
     int32_t degree;
+    uint32_t degree_inv;  // ceil(2^20 / degree): s / degree == (s * degree_inv) >> 20 for s < 1024
     const uint8_t* queries;
     int64_t nq;
     int64_t q_base, q_count;  // this launch serves queries [q_base, q_base + q_count)
@@ -97,6 +102,7 @@ struct BeamSearch {
     Row row;
     uint64_t L[LPL];
     int n_windows;
+    uint32_t w0_lo, w0_size;  // first window: ids [w0_lo, w0_lo + w0_size) are bits 0..
     int n_table;  // ids in the visited hash
     int n_dist, n_parents, n_resets;
 
@@ -108,6 +114,7 @@ struct BeamSearch {
         wtab = parents + 64;
         bitmap = wtab + 32;
         n_windows = n_table = n_dist = n_parents = n_resets = 0;
+        w0_lo = w0_size = 0;
     }
 
     __device__ __forceinline__ void clear_table() {
@@ -115,10 +122,13 @@ struct BeamSearch {
         n_table = 0;
     }
 
-    // Bit of `id` in the visited bitmap, or -1 if no window covers it.
+    // Bit of `id` in the visited bitmap, or -1 if no window covers it.  The first window
+    // (the nearest cluster, where nearly all ids fall) is kept in registers.
     __device__ __forceinline__ int window_bit(uint32_t id) const {
-        int bit = -1;
-        for (int w = 0; w < n_windows; ++w) {
+        const uint32_t rel0 = id - w0_lo;
+        if (__builtin_expect(__all(rel0 < w0_size || n_windows <= 1), 1)) return rel0 < w0_size ? (int)rel0 : -1;
+        int bit = rel0 < w0_size ? (int)rel0 : -1;
+        for (int w = 1; w < n_windows; ++w) {
             const uint32_t rel = id - wtab[3 * w];
             if (rel < wtab[3 * w + 1]) bit = (int)(wtab[3 * w + 2] + rel);
         }
@@ -186,6 +196,7 @@ struct BeamSearch {
             uint32_t id[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
+                if (j0 + u * RPS >= m) break;  // whole step beyond the last row
                 const int j = j0 + u * RPS + grp;
                 const bool live = j < m;
                 id[u] = live ? cid[j] : 0u;
@@ -193,6 +204,7 @@ struct BeamSearch {
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
+                if (j0 + u * RPS >= m) break;
                 const int j = j0 + u * RPS + grp;
                 const uint32_t okey = row.key(x[u], lane);
                 const uint64_t packed = ((uint64_t)okey << 32) | ((uint64_t)id[u] << 1);
@@ -266,6 +278,10 @@ struct BeamSearch {
                     wtab[3 * w + 1] = size;
                     wtab[3 * w + 2] = bit;
                 }
+                if (w == 0) {
+                    w0_lo = (uint32_t)lo;
+                    w0_size = size;
+                }
                 bit += size;
             }
             n_windows = p.route_c;
@@ -333,7 +349,7 @@ struct BeamSearch {
                 const int s = t * 64 + lane;
                 nb[t] = -1;
                 if (s < nref) {
-                    const int pi = s / p.degree;
+                    const int pi = (int)(((uint32_t)s * p.degree_inv) >> 20);
                     nb[t] = __builtin_nontemporal_load(p.graph + (int64_t)parents[pi] * p.degree + (s - pi * p.degree));
                 }
             }
@@ -342,6 +358,9 @@ struct BeamSearch {
             for (int t = 0; t < CPL; ++t) filter_into(nb[t], t * 64 + lane < nref, m);
             lds_sync();
             m = score(m);
+#ifdef ANN_DEBUG_KEPT
+            n_resets += (m == 0 ? 1 : 0) + (m <= 8 ? 1 << 8 : 0) + (m <= 16 ? 1 << 16 : 0) + (m <= 64 ? 1 << 24 : 0);
+#endif
             lds_sync();
             merge_all(m);
         }
@@ -368,10 +387,10 @@ struct BeamSearch {
 
 // Workgroup b runs on XCD b % 8 (round-robin dispatch), so consecutive queries are
 // kept on one XCD and its L2: query = (b % 8) * q_per_xcd + b / 8.
-// The small uint8 variants are asked to fit 8 wavefronts per SIMD (64 VGPRs, 96 SGPRs): with about
-// 5 KB of LDS per query that is the 32 queries per CU the latency-bound loop wants.
+// The small uint8 variants are asked to fit 7 wavefronts per SIMD (8 would push scalar registers into spills): with about
+// 5 KB of LDS per query that gives 28 queries in flight per CU.
 template <class Row, int LPL, int CPL>
-__global__ void __launch_bounds__(64, (Row::kDtype == kU8 && LPL <= 4 && CPL <= 2) ? 8 : 1)
+__global__ void __launch_bounds__(64, (ANN_MIN_WAVES > 1 && Row::kDtype == kU8 && LPL <= 4 && CPL <= 2) ? ANN_MIN_WAVES : 1)
     beam_search_kernel(const SearchParams p) {
     extern __shared__ uint32_t lds[];
     const int64_t b = blockIdx.x;

@@ -28,7 +28,8 @@ __device__ __forceinline__ int rank_below(uint64_t mask) {
 // after which each lane picks the half it did not own.  No LDS traffic.
 template <int CTRL>
 __device__ __forceinline__ uint32_t dpp_move(uint32_t v) {
-    return (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, CTRL, 0xf, 0xf, false);
+    // every lane has a source inside its row for the controls used here, so the "old" value is dead
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xf, 0xf, true);
 }
 #ifndef ANN_XOR_IMPL
 #define ANN_XOR_IMPL 1
@@ -40,6 +41,10 @@ __device__ __forceinline__ uint32_t xor_lane(uint32_t v, int lane) {
     return (uint32_t)__builtin_amdgcn_ds_bpermute((lane ^ MASK) << 2, (int)v);
 #elif ANN_XOR_IMPL == 2
     if constexpr ((MASK & 48) != 0) return (uint32_t)__builtin_amdgcn_ds_bpermute((lane ^ MASK) << 2, (int)v);
+#elif ANN_XOR_IMPL == 3
+    // LDS crossbar, no VALU work: ds_swizzle in bit-mask mode inside 32 lanes, ds_bpermute beyond
+    if constexpr (MASK < 32) return (uint32_t)__builtin_amdgcn_ds_swizzle((int)v, 0x1F | (MASK << 10));
+    else return (uint32_t)__builtin_amdgcn_ds_bpermute((lane ^ MASK) << 2, (int)v);
 #endif
     constexpr int low = MASK & 15;
     if constexpr (low == 1) v = dpp_move<0xB1>(v);        // quad_perm [1,0,3,2]
@@ -69,10 +74,21 @@ __device__ __forceinline__ uint64_t xor_lane64(uint64_t v, int lane) {
 
 // Butterfly sum over groups of G consecutive lanes; every lane of a group ends up
 // with the same value, and the order of additions is the same for every group.
+template <int MASK>
+__device__ __forceinline__ uint32_t xor_lane_dpp(uint32_t v, int lane) {
+    constexpr int low = MASK & 15;
+    if constexpr (low == 1) v = dpp_move<0xB1>(v);
+    else if constexpr (low == 2) v = dpp_move<0x4E>(v);
+    else if constexpr (low == 4) v = dpp_move<0x1B>(dpp_move<0x141>(v));
+    else if constexpr (low == 8) v = dpp_move<0x128>(v);
+    else static_assert(low == 0, "unsupported lane mask");
+    if constexpr ((MASK & 48) != 0) v = (uint32_t)__builtin_amdgcn_ds_bpermute((lane ^ (MASK & 48)) << 2, (int)v);
+    return v;
+}
 template <int G, int M = 1, class T>
 __device__ __forceinline__ T group_sum(T v, int lane) {
     if constexpr (M < G) {
-        const uint32_t o = xor_lane<M>(__builtin_bit_cast(uint32_t, v), lane);
+        const uint32_t o = xor_lane_dpp<M>(__builtin_bit_cast(uint32_t, v), lane);
         return group_sum<G, M * 2>(v + __builtin_bit_cast(T, o), lane);
     } else {
         return v;
