@@ -78,9 +78,9 @@ typedef struct {
 
 /*
  * Validates `desc`, chooses the kernel variant and returns a handle.
- * The borrowed arrays are not copied.  For a routed uint8 index of 128 dimensions a
- * small device array (one int32 per cluster) is allocated and filled on the default
- * stream, which is synchronised before returning; nothing else touches the device.
+ * The borrowed arrays are not copied.  For a routed index whose rows are a multiple of
+ * 32 bytes a small device array (4 bytes per cluster) is allocated and filled on the
+ * default stream, which is synchronised before returning; nothing else touches the device.
  * Must be called with the device that owns the arrays current.
  * Errors: ANN_EINVAL, ANN_EUNSUPPORTED, ANN_ENOMEM, ANN_EHIP.
  */

@@ -9,6 +9,7 @@
 #include <new>
 
 #include "ann.h"
+#include "route_mfma.h"
 #include "route_mfma_u8.h"
 #include "variants.h"
 
@@ -61,7 +62,8 @@ struct ann_index {
     const ann::RowVariant* variant;
     int hash_bits_bias;  // ANN_HASH_BITS_BIAS: extra (or fewer) bits for the visited hash, for tuning
     int window_bits;     // ANN_WINDOW_BITS: size of the visited bitmap over the routed clusters' ids
-    int32_t* centroid_bias;  // DEVICE, owned: per-centroid term of the matrix-core routing, or null
+    int32_t* centroid_bias;  // DEVICE, owned: per-centroid term of the uint8 d=128 matrix-core routing, or null
+    void* route_bias;        // DEVICE, owned: the same for the general matrix-core routing, or null
 };
 
 using namespace ann;
@@ -124,7 +126,22 @@ extern "C" int ann_index_load(const ann_index_desc_t* desc, ann_index_t** out_ha
     if (window_bits > kMaxWindowBits) window_bits = kMaxWindowBits;
     h->window_bits = d.entry_mode == ANN_ENTRY_ROUTED ? (window_bits + 31) / 32 * 32 : 0;
     h->centroid_bias = nullptr;
-    if (d.entry_mode == ANN_ENTRY_ROUTED && d.dtype == ANN_U8 && d.dim == 128 && !getenv("ANN_NO_MFMA_ROUTE")) {
+    h->route_bias = nullptr;
+    const bool mfma_route = d.entry_mode == ANN_ENTRY_ROUTED && !getenv("ANN_NO_MFMA_ROUTE");
+    if (mfma_route && !(d.dtype == ANN_U8 && d.dim == 128) && row_bytes % 32 == 0) {
+        hipError_t e = hipMalloc(&h->route_bias, 4 * (size_t)route_mfma_padded(d.n_clusters));
+        if (e == hipSuccess)
+            e = launch_route_bias(d.dtype, d.metric, static_cast<const uint8_t*>(d.centroids), d.n_clusters,
+                                  (int)row_bytes, h->route_bias, nullptr);
+        if (e == hipSuccess) e = hipStreamSynchronize(nullptr);
+        if (e != hipSuccess) {
+            if (h->route_bias) (void)hipFree(h->route_bias);
+            delete h;
+            return fail(e == hipErrorOutOfMemory ? ANN_ENOMEM : ANN_EHIP, "ann_index_load: preparing the routing failed: %s",
+                        hipGetErrorString(e));
+        }
+    }
+    if (mfma_route && d.dtype == ANN_U8 && d.dim == 128) {
         // routing runs on the matrix cores; its per-centroid term is computed once, here
         hipError_t e = hipMalloc(reinterpret_cast<void**>(&h->centroid_bias),
                                  sizeof(int32_t) * (size_t)route_mfma_u8_padded(d.n_clusters));
@@ -148,6 +165,7 @@ extern "C" int ann_free(ann_index_t* h) {
     if (h->magic != kMagic) return fail(ANN_EINVAL, "ann_free: not a live handle");
     h->magic = 0;
     if (h->centroid_bias) (void)hipFree(h->centroid_bias);
+    if (h->route_bias) (void)hipFree(h->route_bias);
     delete h;
     return ANN_OK;
 }
@@ -206,6 +224,14 @@ extern "C" int ann_route(ann_index_t* h, const void* queries, int64_t nq, int32_
         const hipError_t e = launch_route_mfma_u8(h->d.metric, h->d.route_c, static_cast<const uint8_t*>(h->d.centroids),
                                                   h->centroid_bias, h->d.n_clusters, static_cast<const uint8_t*>(queries),
                                                   nq, out_clusters, static_cast<hipStream_t>(stream));
+        if (e != hipSuccess) return fail(ANN_EHIP, "ann_route: launch failed: %s", hipGetErrorString(e));
+        return ANN_OK;
+    }
+    if (h->route_bias) {
+        const hipError_t e = launch_route_mfma(h->d.dtype, h->d.metric, h->d.route_c,
+                                               static_cast<const uint8_t*>(h->d.centroids), h->route_bias, h->d.n_clusters,
+                                               h->row_bytes, static_cast<const uint8_t*>(queries), nq, out_clusters,
+                                               static_cast<hipStream_t>(stream));
         if (e != hipSuccess) return fail(ANN_EHIP, "ann_route: launch failed: %s", hipGetErrorString(e));
         return ANN_OK;
     }

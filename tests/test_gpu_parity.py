@@ -261,8 +261,10 @@ def test_float_parity(oracle, torch_cuda, dt, dim, metric, itopk, width, degree,
 
 
 @pytest.mark.parametrize("metric", [0, 1])
-@pytest.mark.parametrize("n_clusters,route_c,nq", [(300, 4, 100), (32, 1, 1), (1000, 8, 777), (5, 5, 64), (4097, 3, 300)])
-def test_uint8_matrix_core_routing_is_exact(oracle, torch_cuda, monkeypatch, metric, n_clusters, route_c, nq):
+@pytest.mark.parametrize("n_clusters,route_c,nq,dim", [(300, 4, 100, 128), (32, 1, 1, 128), (1000, 8, 777, 128),
+                                                        (5, 5, 64, 128), (4097, 3, 300, 128), (333, 2, 130, 64),
+                                                        (200, 8, 65, 256), (70, 1, 40, 32)])
+def test_uint8_matrix_core_routing_is_exact(oracle, torch_cuda, monkeypatch, metric, n_clusters, route_c, nq, dim):
     """uint8 d=128 routing runs on the matrix cores (shifted to int8, exact int32 sums) and must give
     the oracle's clusters in the oracle's order, ties by cluster index included; the plain kernel
     (matrix cores switched off) must give the same."""
@@ -270,13 +272,13 @@ def test_uint8_matrix_core_routing_is_exact(oracle, torch_cuda, monkeypatch, met
 
     torch = torch_cuda
     rng = np.random.default_rng(n_clusters + metric)
-    cen = rng.integers(0, 256, (n_clusters, 128), dtype=np.uint8)
+    cen = rng.integers(0, 256, (n_clusters, dim), dtype=np.uint8)
     cen[rng.integers(0, n_clusters, n_clusters // 3)] = cen[0]           # equal centroids: equal keys
     cen[:, :] = np.where(rng.random(cen.shape) < 0.1, rng.choice([0, 255], cen.shape), cen)  # extremes of the range
-    q = rng.integers(0, 256, (nq, 128), dtype=np.uint8)
+    q = rng.integers(0, 256, (nq, dim), dtype=np.uint8)
     q[: nq // 4] = cen[rng.integers(0, n_clusters, nq // 4)]
     want = oracle.route(cen, q, route_c, metric)
-    xt = torch.zeros((64, 128), dtype=torch.uint8, device="cuda")
+    xt = torch.zeros((64, dim), dtype=torch.uint8, device="cuda")
     gt = torch.zeros((64, 4), dtype=torch.int32, device="cuda")
     off = torch.zeros(n_clusters + 1, dtype=torch.int64, device="cuda")
     for no_mfma in (False, True):
@@ -289,25 +291,39 @@ def test_uint8_matrix_core_routing_is_exact(oracle, torch_cuda, monkeypatch, met
         assert np.array_equal(got, want), (no_mfma, np.argwhere(got != want)[:5].tolist())
 
 
-def test_route_matches_oracle(oracle, torch_cuda):
+@pytest.mark.parametrize("no_mfma", [False, True])
+@pytest.mark.parametrize("metric", [0, 1])
+def test_route_matches_oracle(oracle, torch_cuda, monkeypatch, metric, no_mfma):
+    """Routing of float data (matrix cores: fp32 accumulation of q.c plus |c|^2; plain kernel:
+    (q-c)^2 in fp32) against the oracle's double-precision keys: the same clusters except where
+    two centroids are within rounding of each other, and never a cluster that is worse than the
+    oracle's by more than the tolerance."""
     from paper_2512_02278_amd import ann
 
     torch = torch_cuda
     rng = np.random.default_rng(3)
-    for dt, dim in (("u8", 128), ("f32", 96), ("f16", 768)):
+    if no_mfma:
+        monkeypatch.setenv("ANN_NO_MFMA_ROUTE", "1")
+    for dt, dim, nq in (("u8", 128, 100), ("f32", 96, 333), ("f16", 768, 100), ("f32", 8, 70), ("f16", 16, 129)):
         x, cen, off = clustered(rng, 2000, dim, dt, n_centres=300)
-        q = queries_near(rng, x, 100, dt)
-        want = oracle.route(cen, q, 4, 0)
+        q = queries_near(rng, x, nq, dt)
+        want = oracle.route(cen, q, 4, metric)
         xt, ct = torch.from_numpy(x).cuda(), torch.from_numpy(cen).cuda()
         gt = torch.zeros((2000, 4), dtype=torch.int32, device="cuda")
-        h = ann.ann_index_load(xt, gt, entry_mode=1, centroids=ct, cluster_offsets=torch.from_numpy(off).cuda(),
-                               route_c=4)
+        h = ann.ann_index_load(xt, gt, metric=metric, entry_mode=1, centroids=ct,
+                               cluster_offsets=torch.from_numpy(off).cuda(), route_c=4)
         got = ann.ann_route(h, torch.from_numpy(q).cuda()).cpu().numpy()
         ann.ann_free(h)
         if dt == "u8":
             assert np.array_equal(got, want)
         else:
             assert (got == want).mean() > 0.98
+            assert got.min() >= 0 and got.max() < 300 and all(len(set(r.tolist())) == 4 for r in got)
+            # rank by rank the chosen centroid is as near as the oracle's, within the dtype's tolerance
+            kg = oracle.keys(cen, q, got, metric)
+            kw = oracle.keys(cen, q, want, metric)
+            scale = np.abs(kw) + (cen.astype(np.float64) ** 2).sum(1).max()
+            assert (np.abs(kg - kw) <= 10 * TOL[dt] * scale).all()
 
 
 # ----------------------------------------------------------------------------- full-size config, sampled
