@@ -98,9 +98,11 @@ int ann_index_load(const ann_index_desc_t* desc, ann_index_t** out_handle);
  *   out_dists  DEVICE, nq*k keys: int32 for ANN_U8 (pad INT32_MAX), float otherwise (pad +inf)
  *   stream     hipStream_t, NULL for the default stream
  * Results are valid once the stream has been synchronised.  nq == 0 succeeds and
- * launches nothing.  In routed mode a stream-ordered scratch of nq*route_c int32 is
- * allocated and released on `stream`.  On error nothing is launched and the
- * outputs are untouched.  Calls on different streams may share a handle.
+ * launches nothing.  In routed mode stream-ordered scratch (nq*route_c int32 for the
+ * routes; for batches of 16384 queries or more also nq + n_clusters int32 for the
+ * cluster-grouped execution order) is allocated and released on `stream`.  On an
+ * argument error nothing is launched and the outputs are untouched.  Calls on
+ * different streams may share a handle.
  */
 int ann_search(ann_index_t* handle, const void* queries, int64_t nq, int k, int itopk, int width, int max_iters,
                int32_t* out_ids, void* out_dists, void* stream);
@@ -123,7 +125,7 @@ int ann_route(ann_index_t* handle, const void* queries, int64_t nq, int32_t* out
 /*
  * The search step alone for a routed index, with the routing already done: `routes`
  * (DEVICE, nq*route_c int32, as written by ann_route for the same queries) replaces
- * the internal routing pass and no scratch is allocated.  Stage 1 and stage 3 of the
+ * the internal routing pass and its scratch.  Stage 1 and stage 3 of the
  * paper's workflow (Sec. 3.1) can so be issued separately, e.g. on different streams
  * for consecutive batches.  out_counters may be NULL.
  */

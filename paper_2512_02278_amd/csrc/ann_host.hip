@@ -11,6 +11,7 @@
 #include "ann.h"
 #include "route_mfma.h"
 #include "route_mfma_u8.h"
+#include "schedule.h"
 #include "variants.h"
 
 namespace ann {
@@ -52,6 +53,8 @@ constexpr int64_t kMaxQueriesPerLaunch = 1 << 22;
 // Visited bitmap over the routed clusters: 8192 ids cover a cluster of the 100M / 16384
 // partition (about 6100 ids) with room to spare; ids beyond it use the hash.
 constexpr int kDefaultWindowBits = 8192, kMaxWindowBits = 1 << 17;
+// From this batch size on, a routed batch is executed grouped by cluster (schedule.hip).
+constexpr int64_t kMinQueriesForClusterOrder = 16384;
 
 }  // namespace ann
 
@@ -280,6 +283,19 @@ int search_impl(ann_index_t* h, const void* queries, int64_t nq, const int32_t* 
         }
         route = scratch;
     }
+    // routed batches that are large enough run grouped by cluster, for cache reuse
+    int32_t* order = nullptr;
+    if (h->d.entry_mode == ANN_ENTRY_ROUTED && nq >= kMinQueriesForClusterOrder && nq <= 2147483647ll &&
+        !getenv("ANN_NO_CLUSTER_ORDER")) {
+        hipError_t e = hipMallocAsync(reinterpret_cast<void**>(&order), sizeof(int32_t) * ((size_t)nq + h->d.n_clusters), stream);
+        if (e == hipSuccess)
+            e = launch_cluster_order(route, h->d.route_c, nq, h->d.n_clusters, order + nq, order, stream);
+        if (e != hipSuccess) {
+            if (order) (void)hipFreeAsync(order, stream);
+            if (scratch) (void)hipFreeAsync(scratch, stream);
+            return fail(ANN_ENOMEM, "ann_search: preparing the execution order failed: %s", hipGetErrorString(e));
+        }
+    }
 
     int result = ANN_OK;
     for (int64_t q0 = 0; q0 < nq; q0 += kMaxQueriesPerLaunch) {
@@ -313,12 +329,14 @@ int search_impl(ann_index_t* h, const void* queries, int64_t nq, const int32_t* 
         p.out_ids = out_ids;
         p.out_dists = static_cast<uint32_t*>(out_dists);
         p.out_counters = out_counters;
+        p.order = order;
         const hipError_t e = h->variant->search(p, plan.list_variant, (unsigned)(8 * p.q_per_xcd), plan.lds_bytes, stream);
         if (e != hipSuccess) {
             result = fail(ANN_EHIP, "ann_search: launch failed: %s", hipGetErrorString(e));
             break;
         }
     }
+    if (order) (void)hipFreeAsync(order, stream);
     if (scratch) (void)hipFreeAsync(scratch, stream);
     return result;
 }

@@ -54,6 +54,7 @@ struct SearchParams {
     int32_t* out_ids;
     uint32_t* out_dists;
     int32_t* out_counters;  // nq * 4 or null
+    const int32_t* order;   // execution order: the launch's i-th query is order[q_base + i]; null = identity
     int64_t q_per_xcd;      // queries of this launch handed to each of the 8 XCDs
 };
 
@@ -397,7 +398,7 @@ __global__ void __launch_bounds__(64, (ANN_MIN_WAVES > 1 && Row::kDtype == kU8 &
     const int64_t local = (b & 7) * p.q_per_xcd + (b >> 3);
     if (local >= p.q_count) return;
     BeamSearch<Row, LPL, CPL> s(p, lds, lane_id());
-    s.run(p.q_base + local);
+    s.run(p.order ? (int64_t)p.order[p.q_base + local] : p.q_base + local);
 }
 
 }  // namespace ann

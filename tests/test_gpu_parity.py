@@ -142,6 +142,17 @@ def knn_graph(x, degree, metric=0):
     return np.argsort(d, 1, kind="stable")[:, :degree].astype(np.int32)
 
 
+def knn_graph_blocked(x, off, degree):
+    """Exact kNN inside each cluster (clusters are contiguous id ranges), self excluded."""
+    g = np.full((len(x), degree), -1, np.int32)
+    for c in range(len(off) - 1):
+        lo, hi = int(off[c]), int(off[c + 1])
+        if hi - lo > 1:
+            sub = knn_graph(x[lo:hi], min(degree, hi - lo - 1))
+            g[lo:hi, : sub.shape[1]] = sub + lo
+    return g
+
+
 def queries_near(rng, x, nq, dt):
     q = x[rng.integers(0, len(x), nq)].astype(np.float64)
     if dt == "u8":
@@ -222,6 +233,21 @@ def test_visited_bitmap_windows(oracle, torch_cuda, monkeypatch, window_bits, ro
                          centroids=cen, offsets=off, route_c=route_c)
     if window_bits == 8192 and route_c == 3:
         assert (gc[:, 1] - oc["n_dist"]).mean() < 0.05 * oc["n_dist"].mean()
+
+
+def test_cluster_grouped_execution_order(oracle, torch_cuda, monkeypatch):
+    """Batches of 16384 queries or more run grouped by routed cluster; a query keeps its position
+    (and so its entries), so the answers are those of the oracle and of the ungrouped run."""
+    rng = np.random.default_rng(91)
+    x, cen, off = clustered(rng, 30_000, 128, "u8", n_centres=40)
+    g = knn_graph_blocked(x, off, 32)
+    q = queries_near(rng, x, 20_000, "u8")
+    kw = dict(n_entry=32, seed=6, entry_mode=1, centroids=cen, offsets=off, route_c=2)
+    gc, oc = check_exact(oracle, torch_cuda, x, g, q, 10, 64, 2, 60, **kw)
+    grouped = gpu_search(torch_cuda, x, g, q, 10, 64, 2, 60, **kw)
+    monkeypatch.setenv("ANN_NO_CLUSTER_ORDER", "1")
+    plain = gpu_search(torch_cuda, x, g, q, 10, 64, 2, 60, **kw)
+    assert all(np.array_equal(a, b) for a, b in zip(grouped, plain))
 
 
 def test_edge_cases(oracle, torch_cuda):
