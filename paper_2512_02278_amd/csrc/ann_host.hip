@@ -203,7 +203,10 @@ int make_plan(const ann_index* h, int itopk, int width, Plan* plan, const char* 
     while (((3 << bits) >> 2) < itopk + need) ++bits;
     if (bits > 13) bits = 13;
     plan->hash_bits = bits;
-    plan->lds_bytes = sizeof(uint32_t) * ((size_t(1) << bits) + 3 * (size_t)plan->cap + 64 + 32 + (size_t)h->window_bits / 32);
+    // words: round scratch (keys + ids, or a copy of the list), parents, window table, bitmap, hash
+    const size_t scratch = 3 * (size_t)plan->cap > 128 * (size_t)kListVariants[lv][0] ? 3 * (size_t)plan->cap
+                                                                                   : 128 * (size_t)kListVariants[lv][0];
+    plan->lds_bytes = sizeof(uint32_t) * (scratch + 64 + 32 + (size_t)h->window_bits / 32 + (size_t(1) << bits));
     return ANN_OK;
 }
 

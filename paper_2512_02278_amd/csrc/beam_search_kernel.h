@@ -25,8 +25,11 @@
 
 #include "row_ops.h"
 
+#ifndef ANN_INSERT_MAX
+#define ANN_INSERT_MAX 8
+#endif
 #ifndef ANN_MIN_WAVES
-#define ANN_MIN_WAVES 7
+#define ANN_MIN_WAVES 6
 #endif
 
 namespace ann {
@@ -91,6 +94,7 @@ struct BeamSearch {
     static constexpr int RPS = 64 / G;                                // rows per gather step
     static constexpr int U = NCH >= 4 ? 1 : (NCH >= 2 ? 2 : 4);       // gather steps in flight
     static constexpr int BR = LPL >= 2 ? 2 : 1;                       // registers of a sort batch
+    static constexpr int kInsertMax = ANN_INSERT_MAX;                 // at most this many new keys are inserted one by one
 
     const SearchParams& p;
     int lane;
@@ -107,13 +111,21 @@ struct BeamSearch {
     int n_table;  // ids in the visited hash
     int n_dist, n_parents, n_resets;
 
+    // LDS layout, in 32-bit words.  Everything but the hash sits at a compile-time offset, so the
+    // addresses fold into the DS instructions' immediate offsets:
+    //   [0, kScratchWords)   packed keys of a round (2 words each), then its surviving ids; the same
+    //                        words hold a copy of the whole list while a few keys are inserted
+    //   parents (64)  window table (32)  bitmap (window_bits / 32)  hash (1 << hash_bits)
+    static constexpr int kCap = 64 * CPL;
+    static constexpr int kScratchWords = 3 * kCap > 128 * LPL ? 3 * kCap : 128 * LPL;
+
     __device__ __forceinline__ BeamSearch(const SearchParams& p_, uint32_t* lds, int lane_) : p(p_), lane(lane_) {
-        table = lds;
-        ckey = reinterpret_cast<uint64_t*>(lds + (1 << p.hash_bits));
-        cid = lds + (1 << p.hash_bits) + 2 * p.cap;
-        parents = cid + p.cap;
+        ckey = reinterpret_cast<uint64_t*>(lds);
+        cid = lds + 2 * kCap;
+        parents = lds + kScratchWords;
         wtab = parents + 64;
         bitmap = wtab + 32;
+        table = bitmap + (p.window_bits >> 5);
         n_windows = n_table = n_dist = n_parents = n_resets = 0;
         w0_lo = w0_size = 0;
     }
@@ -248,7 +260,49 @@ struct BeamSearch {
         lds_sync();
     }
 
+    // list <- itopk smallest of list U ckey[0..s) for a handful of keys (1 <= s <= 64, meant for
+    // s <= 8), without sorting: an entry moves up by the number of new keys below it, a new key
+    // lands at (entries below it) + (new keys below it); the moves go through a copy in LDS.
+    __device__ __forceinline__ void insert_few(int s) {
+        uint64_t* lcopy = ckey;
+        const uint64_t mine = lane < s ? ckey[lane] : kInfKey;
+        lds_sync();  // the new keys are in registers; their words may now be overwritten
+        for (int i = p.itopk + lane; i < 64 * LPL; i += 64) lcopy[i] = kInfKey;
+        int cnt[LPL];
+#pragma unroll
+        for (int r = 0; r < LPL; ++r) cnt[r] = 0;
+        int rank = 0, pos = 0;
+        for (int j = 0; j < s; ++j) {
+            const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)mine, j);
+            const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(mine >> 32), j);
+            const uint64_t c = ((uint64_t)hi << 32) | lo;
+            int below = 64 * LPL;
+#pragma unroll
+            for (int r = 0; r < LPL; ++r) {
+                const bool lt = c < L[r];
+                cnt[r] += lt ? 1 : 0;
+                below -= __builtin_popcountll(__ballot(lt));
+            }
+            rank += c < mine ? 1 : 0;
+            pos = lane == j ? below : pos;
+        }
+#pragma unroll
+        for (int r = 0; r < LPL; ++r) {
+            const int idx = lane * LPL + r + cnt[r];
+            if (idx < p.itopk) lcopy[idx] = L[r];
+        }
+        if (lane < s && pos + rank < p.itopk) lcopy[pos + rank] = mine;
+        lds_sync();
+#pragma unroll
+        for (int r = 0; r < LPL; ++r) L[r] = lcopy[lane * LPL + r];
+        lds_sync();
+    }
+
     __device__ __forceinline__ void merge_all(int m) {
+        if (m >= 1 && m <= kInsertMax) {
+            insert_few(m);
+            return;
+        }
         int base = 0;
         if constexpr (BR == 2) {
             for (; m - base > 64; base += 128) merge_batch<2, 128>(base, m);

@@ -22,17 +22,19 @@ __device__ __forceinline__ int rank_below(uint64_t mask) {
     return (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
 }
 
-// Value of `v` held by lane (lane ^ MASK), MASK a compile-time constant.  Inside a row of 16
-// lanes the exchange is a DPP move (quad permutes, half-row and row mirrors, rotate by 8);
-// across rows it is a v_permlane16_swap / v_permlane32_swap of the register with itself,
-// after which each lane picks the half it did not own.  No LDS traffic.
+// Value of `v` held by lane (lane ^ MASK), MASK a compile-time constant.  ANN_XOR_IMPL picks
+// the mechanism: 0 = ds_bpermute everywhere; 1 = DPP moves inside a row of 16 lanes (quad
+// permutes, half-row and row mirrors, rotate by 8) and v_permlane16/32_swap across rows;
+// 2 (default, fastest measured) = DPP inside a row, ds_bpermute across rows: the search loop
+// is bound by vector-ALU issue, and the LDS crossbar takes the cross-row moves off the VALU;
+// 3 = ds_swizzle / ds_bpermute only.
 template <int CTRL>
 __device__ __forceinline__ uint32_t dpp_move(uint32_t v) {
     // every lane has a source inside its row for the controls used here, so the "old" value is dead
     return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xf, 0xf, true);
 }
 #ifndef ANN_XOR_IMPL
-#define ANN_XOR_IMPL 1
+#define ANN_XOR_IMPL 2
 #endif
 template <int MASK>
 __device__ __forceinline__ uint32_t xor_lane(uint32_t v, int lane) {
