@@ -12,10 +12,20 @@
 //
 // Tiling.  A = 32 centroids x 32 bytes, B = 32 queries x 32 bytes per instruction;
 // a wavefront keeps 64 queries (two B sets) in registers for the whole kernel and
-// walks all centroids, 32 at a time.  In the 32x32 result a lane holds 16 centroids
+// walks all centroids, 32 at a time.  The four wavefronts of a workgroup (256 queries)
+// share each centroid tile: it is fetched from L2 once (one 16-byte piece per thread,
+// shifted to int8 on the way), double-buffered in LDS in the order the matrix
+// instruction consumes it, and read back conflict-free.  Without the sharing the kernel
+// is bound by L2 bandwidth.  In the 32x32 result a lane holds 16 centroids
 // of ONE query (column = lane % 32), so the running best list of a query lives in
 // two lanes' registers and needs no exchange until the end.  Rows are visited in
 // ascending cluster order, so a strict "<" keeps the lower index among equal keys.
+//
+// Selection is the expensive part (16 results per lane and tile against 4 matrix
+// instructions), so it works on packed words: the bias array holds bias*16 + v, v being
+// the result slot of that row inside a lane, and one multiply-add gives score*16 + v.  A
+// tree of v_min3 finds a tile's best (score, row) in a lane, and only a tile whose best
+// beats the worst kept score is looked at value by value.
 #include <hip/hip_runtime.h>
 
 #include "route_mfma_u8.h"
@@ -25,15 +35,17 @@ namespace ann {
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
-constexpr int kPadBias = 0x3fffffff;  // bias of the padding rows: never among the best
+constexpr int kPadScore = 0x03ffffff;  // score of the padding rows: above every real one, and score*16 fits
 
 template <int METRIC>
 __global__ void __launch_bounds__(256) centroid_bias_kernel(const uint8_t* centroids, int n_clusters, int padded,
                                                             int32_t* bias) {
     const int c = blockIdx.x * 256 + threadIdx.x;
     if (c >= padded) return;
+    // result slot of a row inside a lane: tile row 8 (v / 4) + 4 half + v % 4  <->  v
+    const int slot = 4 * ((c & 31) >> 3) + (c & 3);
     if (c >= n_clusters) {
-        bias[c] = kPadBias;
+        bias[c] = kPadScore * 16 + slot;
         return;
     }
     const uint32_t* row = reinterpret_cast<const uint32_t*>(centroids + (int64_t)c * 128);
@@ -45,7 +57,7 @@ __global__ void __launch_bounds__(256) centroid_bias_kernel(const uint8_t* centr
         else
             acc = __builtin_amdgcn_sdot4((int)w, 0x01010101, acc, false);
     }
-    bias[c] = METRIC == 0 ? acc : -128 * acc;
+    bias[c] = (METRIC == 0 ? acc : -128 * acc) * 16 + slot;
 }
 
 template <int METRIC, int RC>
@@ -55,10 +67,11 @@ __global__ void __launch_bounds__(256) route_mfma_u8_kernel(const uint8_t* __res
                                                             int32_t* __restrict__ out) {
     constexpr int NQS = 2;  // query sets of 32 per wavefront
     __shared__ uint64_t pool[4][NQS * 32][2][RC];
+    __shared__ v4i atile[2][8 * 32];  // [piece 0..7][row 0..31] 16-byte units of one centroid tile
+    __shared__ v4i btile[2][8];       // the tile's 32 bias words
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int col = lane & 31, half = lane >> 5;
-    const int64_t q0 = ((int64_t)blockIdx.x * 4 + wave) * (NQS * 32);
-    if (q0 >= nq) return;  // whole wavefront; no block-wide barrier is used below
+    const int64_t q0 = ((int64_t)blockIdx.x * 4 + wave) * (NQS * 32);  // may lie beyond nq: such wavefronts only help loading
 
     // B: lane holds, for query (q0 + 32 s + col), the 16 bytes number 2 t + half of the row
     v4i b[NQS][4];
@@ -81,44 +94,78 @@ __global__ void __launch_bounds__(256) route_mfma_u8_kernel(const uint8_t* __res
             best_i[s][r] = 0x7fffffff;
         }
 
+    // thread x fetches piece x % 8 of tile row x / 8 (eight threads read one 128-byte row)
+    const int ld_row = threadIdx.x >> 3, ld_piece = threadIdx.x & 7;
     const int n_tiles = (n_clusters + 31) / 32;
+    auto fetch = [&](int ct) {
+        int r = ct * 32 + ld_row;
+        if (r >= n_clusters) r = n_clusters - 1;
+        return *reinterpret_cast<const v4i*>(centroids + (int64_t)r * 128 + ld_piece * 16) ^ (int)0x80808080;
+    };
+    const v4i* bias4 = reinterpret_cast<const v4i*>(bias);
+    atile[0][ld_piece * 32 + ld_row] = fetch(0);
+    if (threadIdx.x < 8) btile[0][threadIdx.x] = bias4[threadIdx.x];
+    __syncthreads();
     for (int ct = 0; ct < n_tiles; ++ct) {
-        int arow = ct * 32 + col;
-        if (arow >= n_clusters) arow = n_clusters - 1;
+        v4i next, next_bias;
+        if (ct + 1 < n_tiles) {
+            next = fetch(ct + 1);
+            if (threadIdx.x < 8) next_bias = bias4[(ct + 1) * 8 + threadIdx.x];
+        }
         v4i a[4];
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            a[t] = *reinterpret_cast<const v4i*>(centroids + (int64_t)arow * 128 + (2 * t + half) * 16);
-            a[t] ^= (int)0x80808080;
-        }
+        for (int t = 0; t < 4; ++t) a[t] = atile[ct & 1][(2 * t + half) * 32 + col];
         // result element v of a lane is row 8 (v / 4) + 4 half + v % 4 of the tile
         v4i bs[4];
 #pragma unroll
-        for (int g = 0; g < 4; ++g) bs[g] = *reinterpret_cast<const v4i*>(bias + ct * 32 + 8 * g + 4 * half);
+        for (int g = 0; g < 4; ++g) bs[g] = btile[ct & 1][2 * g + half];
 #pragma unroll
         for (int s = 0; s < NQS; ++s) {
             v16i acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
             for (int t = 0; t < 4; ++t) acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[t], b[s][t], acc, 0, 0, 0);
+            // packed[v] = score * 16 + v
+            int32_t packed[16];
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int32_t score = bs[v / 4][v % 4] - (METRIC == 0 ? 2 : 1) * acc[v];
-                const int32_t idx = ct * 32 + 8 * (v / 4) + 4 * half + (v % 4);
-                if (score < best_s[s][RC - 1]) {
-                    // insertion; equal scores stay behind the earlier (smaller) index
-                    int32_t cs = score, ci = idx;
+            for (int v = 0; v < 16; ++v) packed[v] = bs[v / 4][v % 4] - (METRIC == 0 ? 32 : 16) * acc[v];
+            int32_t m01 = min(min(packed[0], packed[1]), packed[2]);
+            int32_t m02 = min(min(packed[3], packed[4]), packed[5]);
+            int32_t m03 = min(min(packed[6], packed[7]), packed[8]);
+            int32_t m04 = min(min(packed[9], packed[10]), packed[11]);
+            int32_t m05 = min(min(packed[12], packed[13]), packed[14]);
+            const int32_t tile_best = min(min(min(m01, m02), min(m03, m04)), min(m05, packed[15]));
+            const int32_t tile_score = tile_best >> 4;
+            if constexpr (RC == 1) {
+                // strict "<" on the score alone: among equal scores the earlier tile stays
+                const bool better = tile_score < best_s[s][0];
+                best_s[s][0] = better ? tile_score : best_s[s][0];
+                best_i[s][0] = better ? ct * 32 + 8 * ((tile_best & 15) >> 2) + 4 * half + (tile_best & 3) : best_i[s][0];
+            } else if (__any(tile_score < best_s[s][RC - 1])) {
 #pragma unroll
-                    for (int r = 0; r < RC; ++r) {
-                        const bool first = cs < best_s[s][r];
-                        const int32_t ts = best_s[s][r], ti = best_i[s][r];
-                        best_s[s][r] = first ? cs : ts;
-                        best_i[s][r] = first ? ci : ti;
-                        cs = first ? ts : cs;
-                        ci = first ? ti : ci;
+                for (int v = 0; v < 16; ++v) {
+                    const int32_t score = packed[v] >> 4;
+                    const int32_t idx = ct * 32 + 8 * (v / 4) + 4 * half + (v % 4);
+                    if (score < best_s[s][RC - 1]) {
+                        // insertion; equal scores stay behind the earlier (smaller) index
+                        int32_t cs = score, ci = idx;
+#pragma unroll
+                        for (int r = 0; r < RC; ++r) {
+                            const bool first = cs < best_s[s][r];
+                            const int32_t ts = best_s[s][r], ti = best_i[s][r];
+                            best_s[s][r] = first ? cs : ts;
+                            best_i[s][r] = first ? ci : ti;
+                            cs = first ? ts : cs;
+                            ci = first ? ti : ci;
+                        }
                     }
                 }
             }
         }
+        if (ct + 1 < n_tiles) {
+            atile[(ct + 1) & 1][ld_piece * 32 + ld_row] = next;
+            if (threadIdx.x < 8) btile[(ct + 1) & 1][threadIdx.x] = next_bias;
+        }
+        __syncthreads();
     }
 
     // the two lanes of a query merge their ascending lists through LDS
