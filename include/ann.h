@@ -144,6 +144,27 @@ const char* ann_last_error(void);
 int64_t ann_lds_bytes(ann_index_t* handle, int itopk, int width);
 
 /*
+ * Stage 4, local half (Sec. 3.1, "Combine vector candidate results": a rank returns the
+ * vectors of its top-k, not only their ids).  Copies the rows of `count` ids into dense
+ * rows of dim elements; an id outside [0, n) gives a row of zeros.
+ *   ids          DEVICE, count int32 (e.g. the nq*k out_ids of a search)
+ *   out_vectors  DEVICE, count * dim elements of the index dtype, 16-byte aligned
+ */
+int ann_gather_vectors(ann_index_t* handle, const int32_t* ids, int64_t count, void* out_vectors, void* stream);
+
+/*
+ * Stage 4, merge at the origin (Sec. 3.1 / Sec. 3.2 "Stage 4": the top k*c candidates a query
+ * gets back from the c partitions it was sent to are reduced to the final top-k).  Needs no
+ * index.  For each of nq queries, `per_query` candidates (any order, 1 .. 512; id < 0 =
+ * padding, ignored) are reduced to the k smallest under (key, id), k <= per_query; results
+ * are padded like ann_search's.  Candidate ids of one query must be distinct.
+ *   ids, keys          DEVICE, nq*per_query int32 / (int32 if key_dtype == ANN_U8, else float)
+ *   out_ids, out_keys  DEVICE, nq*k
+ */
+int ann_merge_topk(int key_dtype, const int32_t* ids, const void* keys, int64_t nq, int per_query, int k,
+                   int32_t* out_ids, void* out_keys, void* stream);
+
+/*
  * Measurement aid, not part of the search: copies `bytes` (a multiple of 16, both
  * pointers DEVICE and 16-byte aligned) with a plain grid-stride kernel named
  * ann_calibration_copy_kernel.  A profiler's HBM byte counters can be calibrated

@@ -170,3 +170,30 @@ def route(centroids, queries, route_c, metric=L2):
 
 def threads(n_threads=0) -> int:
     return int(_load().oracle_threads(ctypes.c_int32(n_threads)))
+
+
+def merge_topk(ids, keys, k):
+    """Final top-k of [nq, per_query] candidates under (key, id); id < 0 is padding."""
+    ids = _c(ids, np.int32)
+    keys = _c(keys)
+    assert ids.shape == keys.shape and keys.dtype in (np.int32, np.float32)
+    nq, per_query = ids.shape
+    out_ids = np.empty((nq, k), np.int32)
+    out_keys = np.empty((nq, k), keys.dtype)
+    _load().oracle_merge_topk.restype = ctypes.c_int
+    rc = _load().oracle_merge_topk(ctypes.c_int32(int(keys.dtype == np.float32)), _p(ids), _p(keys), ctypes.c_int64(nq),
+                                   ctypes.c_int32(per_query), ctypes.c_int32(k), _p(out_ids), _p(out_keys))
+    if rc != 0:
+        raise ValueError("oracle_merge_topk rejected its arguments")
+    return out_ids, out_keys
+
+
+def gather(vectors, ids):
+    """Rows of `vectors` for every id (zeros where the id is outside the partition)."""
+    ids = _c(ids, np.int32)
+    out = np.empty((*ids.shape, vectors.shape[1]), vectors.dtype)
+    _load().oracle_gather.restype = None
+    _load().oracle_gather(_p(vectors), ctypes.c_int64(vectors.shape[0]), ctypes.c_int32(vectors.shape[1]),
+                          ctypes.c_int32(dtype_code(vectors)), ctypes.c_int64(vectors.strides[0]), _p(ids),
+                          ctypes.c_int64(ids.size), _p(out))
+    return out

@@ -448,3 +448,53 @@ int oracle_route(int32_t dim, int32_t dtype, int32_t metric, const void* centroi
         nearest_clusters(&ix, (const char*)queries + qbytes * (size_t)i, out_clusters + i * route_c);
     return 0;
 }
+
+/*
+ * Stage 4 of the paper's workflow (Sec. 3.1, "Combine vector candidate results"), local half.
+ *
+ * oracle_merge_topk: the origin rank reduces the k*c candidates a query got back to the final
+ * top-k.  Plain definition: drop padding (id < 0), sort all candidates of the query by
+ * (key, id), keep the first k, pad.  keys: int32 (is_float == 0) or float.
+ */
+int oracle_merge_topk(int32_t is_float, const int32_t* ids, const void* keys, int64_t nq, int32_t per_query, int32_t k,
+                      int32_t* out_ids, void* out_keys) {
+    if (nq < 0 || per_query < 1 || k < 1 || k > per_query) return -1;
+    item_t* all = (item_t*)malloc(sizeof(item_t) * (size_t)per_query);
+    for (int64_t q = 0; q < nq; ++q) {
+        int32_t cnt = 0;
+        for (int32_t e = 0; e < per_query; ++e) {
+            int32_t id = ids[q * per_query + e];
+            if (id < 0) continue;
+            all[cnt].key = is_float ? (double)((const float*)keys)[q * per_query + e]
+                                    : (double)((const int32_t*)keys)[q * per_query + e];
+            all[cnt].id = id;
+            all[cnt].expanded = 0;
+            ++cnt;
+        }
+        qsort(all, (size_t)cnt, sizeof(item_t), item_cmp);
+        for (int32_t r = 0; r < k; ++r) {
+            int have = r < cnt;
+            out_ids[q * k + r] = have ? all[r].id : -1;
+            if (is_float)
+                ((float*)out_keys)[q * k + r] = have ? (float)all[r].key : INFINITY;
+            else
+                ((int32_t*)out_keys)[q * k + r] = have ? (int32_t)all[r].key : INT32_MAX;
+        }
+    }
+    free(all);
+    return 0;
+}
+
+/* oracle_gather: the vectors of the given ids as dense rows (zeros for id outside [0, n)):
+ * what a rank sends back besides the ids. */
+void oracle_gather(const void* vectors, int64_t n, int32_t dim, int32_t dtype, int64_t row_stride_bytes,
+                   const int32_t* ids, int64_t count, void* out) {
+    size_t rb = elem_size(dtype) * (size_t)dim;
+    for (int64_t i = 0; i < count; ++i) {
+        char* dst = (char*)out + rb * (size_t)i;
+        if (ids[i] >= 0 && (int64_t)ids[i] < n)
+            memcpy(dst, (const char*)vectors + (int64_t)ids[i] * row_stride_bytes, rb);
+        else
+            memset(dst, 0, rb);
+    }
+}

@@ -22,7 +22,7 @@ ANN_OK, ANN_EINVAL, ANN_EUNSUPPORTED, ANN_ENOMEM, ANN_EHIP = 0, -1, -2, -3, -4
 _DTYPES = {torch.uint8: ANN_U8, torch.float16: ANN_F16, torch.float32: ANN_F32}
 
 EXPORTS = ("ann_index_load", "ann_search", "ann_search_counters", "ann_search_routed", "ann_route", "ann_free",
-           "ann_last_error", "ann_lds_bytes", "ann_calibration_copy")
+           "ann_last_error", "ann_lds_bytes", "ann_calibration_copy", "ann_gather_vectors", "ann_merge_topk")
 
 
 class ann_index_desc_t(ctypes.Structure):
@@ -66,6 +66,10 @@ def lib() -> ctypes.CDLL:
         L.ann_free.restype = ctypes.c_int
         L.ann_last_error.argtypes = []
         L.ann_last_error.restype = ctypes.c_char_p
+        L.ann_gather_vectors.argtypes = [vp, vp, i64, vp, vp]
+        L.ann_gather_vectors.restype = ctypes.c_int
+        L.ann_merge_topk.argtypes = [i32, vp, vp, i64, i32, i32, vp, vp, vp]
+        L.ann_merge_topk.restype = ctypes.c_int
         L.ann_calibration_copy.argtypes = [vp, vp, i64, vp]
         L.ann_calibration_copy.restype = ctypes.c_int
         L.ann_lds_bytes.argtypes = [vp, i32, i32]
@@ -201,3 +205,36 @@ def ann_calibration_copy(dst: torch.Tensor, src: torch.Tensor, stream=None) -> N
     if dst.numel() * dst.element_size() != nbytes or not (dst.is_contiguous() and src.is_contiguous()):
         raise ValueError("dst and src must be contiguous and of equal size")
     _check(lib().ann_calibration_copy(_dev_ptr(dst, "dst"), _dev_ptr(src, "src"), nbytes, _stream(stream)))
+
+
+def ann_gather_vectors(h: Handle, ids: torch.Tensor, out_vectors: torch.Tensor = None, stream=None) -> torch.Tensor:
+    """Rows of the index for every id in `ids` (any shape, int32); zeros where id < 0."""
+    if ids.dtype != torch.int32 or not ids.is_contiguous():
+        raise ValueError("ids must be a contiguous int32 tensor")
+    if out_vectors is None:
+        out_vectors = torch.empty((*ids.shape, h.dim), dtype=h.dtype, device=ids.device)
+    if out_vectors.dtype != h.dtype or out_vectors.numel() != ids.numel() * h.dim or not out_vectors.is_contiguous():
+        raise ValueError("out_vectors must be contiguous, of the index dtype, with ids.numel() * dim elements")
+    _check(lib().ann_gather_vectors(h.ptr, _dev_ptr(ids, "ids"), ids.numel(), _dev_ptr(out_vectors, "out_vectors"),
+                                    _stream(stream)))
+    return out_vectors
+
+
+def ann_merge_topk(ids: torch.Tensor, keys: torch.Tensor, k: int, out_ids: torch.Tensor = None,
+                   out_keys: torch.Tensor = None, stream=None):
+    """ids, keys: [nq, per_query] candidates (int32 ids; int32 or float32 keys) -> ([nq, k], [nq, k])."""
+    if ids.dim() != 2 or ids.shape != keys.shape or ids.dtype != torch.int32 or keys.dtype not in (torch.int32, torch.float32):
+        raise ValueError("ids [nq, per_query] int32 and keys of the same shape, int32 or float32")
+    if not (ids.is_contiguous() and keys.is_contiguous()):
+        raise ValueError("ids and keys must be contiguous")
+    nq, per_query = ids.shape
+    if out_ids is None:
+        out_ids = torch.empty((nq, k), dtype=torch.int32, device=ids.device)
+    if out_keys is None:
+        out_keys = torch.empty((nq, k), dtype=keys.dtype, device=ids.device)
+    if out_ids.dtype != torch.int32 or out_keys.dtype != keys.dtype or out_ids.numel() != nq * k or out_keys.numel() != nq * k:
+        raise ValueError("out_ids / out_keys have the wrong dtype or size")
+    key_dtype = ANN_U8 if keys.dtype == torch.int32 else ANN_F32
+    _check(lib().ann_merge_topk(key_dtype, _dev_ptr(ids, "ids"), _dev_ptr(keys, "keys"), nq, per_query, k,
+                                _dev_ptr(out_ids, "out_ids"), _dev_ptr(out_keys, "out_keys"), _stream(stream)))
+    return out_ids, out_keys

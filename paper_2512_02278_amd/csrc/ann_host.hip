@@ -9,6 +9,7 @@
 #include <new>
 
 #include "ann.h"
+#include "combine.h"
 #include "route_mfma.h"
 #include "route_mfma_u8.h"
 #include "schedule.h"
@@ -363,6 +364,38 @@ extern "C" int ann_search_routed(ann_index_t* h, const void* queries, int64_t nq
 extern "C" int ann_search(ann_index_t* h, const void* queries, int64_t nq, int k, int itopk, int width, int max_iters,
                           int32_t* out_ids, void* out_dists, void* stream) {
     return ann_search_counters(h, queries, nq, k, itopk, width, max_iters, out_ids, out_dists, nullptr, stream);
+}
+
+extern "C" int ann_gather_vectors(ann_index_t* h, const int32_t* ids, int64_t count, void* out_vectors, void* stream) {
+    if (!h || h->magic != kMagic) return fail(ANN_EINVAL, "ann_gather_vectors: not a live handle");
+    if (count < 0) return fail(ANN_EINVAL, "ann_gather_vectors: count = %lld", (long long)count);
+    if (count == 0) return ANN_OK;
+    if (!ids || !out_vectors) return fail(ANN_EINVAL, "ann_gather_vectors: null argument");
+    if (!aligned16(out_vectors)) return fail(ANN_EINVAL, "ann_gather_vectors: out_vectors not 16-byte aligned");
+    const hipError_t e = launch_gather_rows(static_cast<const uint8_t*>(h->d.vectors), h->d.n, h->d.row_stride_bytes,
+                                            h->row_bytes, ids, count, static_cast<uint8_t*>(out_vectors),
+                                            static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? ANN_OK : fail(ANN_EHIP, "ann_gather_vectors: launch failed: %s", hipGetErrorString(e));
+}
+
+extern "C" int ann_merge_topk(int key_dtype, const int32_t* ids, const void* keys, int64_t nq, int per_query, int k,
+                              int32_t* out_ids, void* out_keys, void* stream) {
+    if (key_dtype != ANN_U8 && key_dtype != ANN_F16 && key_dtype != ANN_F32)
+        return fail(ANN_EINVAL, "ann_merge_topk: unknown key_dtype %d", key_dtype);
+    if (nq < 0) return fail(ANN_EINVAL, "ann_merge_topk: nq = %lld", (long long)nq);
+    if (per_query < 1 || per_query > kMaxItopk) return fail(ANN_EUNSUPPORTED, "ann_merge_topk: per_query = %d outside 1..%d", per_query, kMaxItopk);
+    if (k < 1 || k > per_query) return fail(ANN_EINVAL, "ann_merge_topk: k = %d outside 1..per_query (%d)", k, per_query);
+    if (nq == 0) return ANN_OK;
+    if (!ids || !keys || !out_ids || !out_keys) return fail(ANN_EINVAL, "ann_merge_topk: null argument");
+    for (int64_t q0 = 0; q0 < nq; q0 += kMaxQueriesPerLaunch) {
+        const int64_t cnt = nq - q0 < kMaxQueriesPerLaunch ? nq - q0 : kMaxQueriesPerLaunch;
+        const hipError_t e = launch_merge_topk(key_dtype != ANN_U8, ids + q0 * per_query,
+                                               static_cast<const uint32_t*>(keys) + q0 * per_query, cnt, per_query, k,
+                                               out_ids + q0 * k, static_cast<uint32_t*>(out_keys) + q0 * k,
+                                               static_cast<hipStream_t>(stream));
+        if (e != hipSuccess) return fail(ANN_EHIP, "ann_merge_topk: launch failed: %s", hipGetErrorString(e));
+    }
+    return ANN_OK;
 }
 
 namespace ann {

@@ -381,3 +381,48 @@ def test_one_million_config_sampled_against_oracle(oracle, torch_cuda):
     assert all(len(set(r.tolist())) == 10 for r in ids_all[::97])
     gt = inputs.ground_truth(part, q[:500], 10)
     assert inputs.recall(ids[:500], gt) > 0.95
+
+
+# ----------------------------------------------------------------------------- stage 4, local half
+@pytest.mark.parametrize("dt,dim", [("u8", 128), ("f32", 96), ("f16", 768), ("u8", 16)])
+def test_gather_vectors_matches_oracle(oracle, torch_cuda, dt, dim):
+    from paper_2512_02278_amd import ann
+
+    torch = torch_cuda
+    rng = np.random.default_rng(50)
+    pad = 32 // NP_DT[dt]().itemsize
+    buf = (rng.integers(0, 256, (3000, dim + pad)).astype(NP_DT[dt]) if dt == "u8"
+           else rng.standard_normal((3000, dim + pad)).astype(NP_DT[dt]))
+    x = buf[:, :dim]
+    ids = rng.integers(-1, 3000, (700, 10)).astype(np.int32)
+    ids[5, 3] = 3000  # outside the partition
+    want = oracle.gather(x, ids)
+    xt = torch.from_numpy(buf).cuda()[:, :dim]
+    h = ann.ann_index_load(xt, torch.zeros((3000, 4), dtype=torch.int32, device="cuda"))
+    got = ann.ann_gather_vectors(h, torch.from_numpy(ids).cuda())
+    torch.cuda.synchronize()
+    ann.ann_free(h)
+    assert np.array_equal(got.cpu().numpy().view(np.uint8), want.view(np.uint8))
+
+
+@pytest.mark.parametrize("per_query,k,is_float", [(30, 10, False), (64, 64, False), (300, 100, True), (512, 7, True),
+                                                  (1, 1, False), (129, 50, False)])
+def test_merge_topk_matches_oracle(oracle, torch_cuda, per_query, k, is_float):
+    from paper_2512_02278_amd import ann
+
+    torch = torch_cuda
+    rng = np.random.default_rng(per_query)
+    nq = 333
+    ids = np.stack([rng.permutation(5000)[:per_query] for _ in range(nq)]).astype(np.int32)
+    ids[rng.random(ids.shape) < 0.15] = -1
+    if is_float:
+        keys = rng.standard_normal(ids.shape).astype(np.float32)
+        keys[rng.random(ids.shape) < 0.3] = 0.5       # ties
+        keys[0, 0] = -0.0
+    else:
+        keys = rng.integers(-50, 50, ids.shape).astype(np.int32)  # many ties, negative keys (inner product)
+    want_i, want_k = oracle.merge_topk(ids, keys, k)
+    got_i, got_k = ann.ann_merge_topk(torch.from_numpy(ids).cuda(), torch.from_numpy(keys).cuda(), k)
+    torch.cuda.synchronize()
+    assert np.array_equal(got_i.cpu().numpy(), want_i)
+    assert np.array_equal(got_k.cpu().numpy(), want_k)

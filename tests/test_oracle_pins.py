@@ -426,3 +426,49 @@ def test_tiny_sift_like_config_behaves_as_expected(oracle):
     assert 0.1 < rec_u < 0.5  # about 1 - (1 - 1/100)^32 = 0.28
     assert rec_r > 0.97
     assert cnt["iters"].max() <= 50
+
+
+# ----------------------------------------------------------------------------- stage 4, local half
+@pytest.mark.parametrize("dt", ["u8", "f32"])
+def test_merge_of_partition_results_is_global_bruteforce(oracle, dt):
+    """Merging the exact top-k of disjoint partitions (ids made global) gives the exact top-k of
+    their union: the definition of the combine step.  Also checked directly against a numpy
+    lexsort, with padding and ties."""
+    rng = np.random.default_rng(40)
+    n, dim, k, parts = 900, 16, 10, 3
+    x = random_vectors(rng, n, dim, dt)
+    if dt == "u8":
+        x %= 6
+    q = random_vectors(rng, 25, dim, dt)
+    if dt == "u8":
+        q %= 6
+    bounds = [0, 250, 255, 900]  # the middle partition has fewer than k vectors: its list is padded
+    ids_p, keys_p = [], []
+    for p in range(parts):
+        lo, hi = bounds[p], bounds[p + 1]
+        i, d = oracle.bruteforce(np.ascontiguousarray(x[lo:hi]), q, k, 0)
+        ids_p.append(np.where(i >= 0, i + lo, -1))
+        keys_p.append(d)
+    ids = np.concatenate(ids_p, 1).astype(np.int32)
+    keys = np.concatenate(keys_p, 1)
+    got_i, got_k = oracle.merge_topk(ids, keys, k)
+    want_i, want_k = oracle.bruteforce(x, q, k, 0)
+    assert np.array_equal(got_i, want_i) and np.array_equal(got_k, want_k)
+    for r in range(len(q)):
+        real = ids[r] >= 0
+        order = np.lexsort((ids[r][real], keys[r][real]))[:k]
+        assert got_i[r].tolist() == ids[r][real][order].tolist()
+    # fewer candidates than k: padded
+    gi, gk = oracle.merge_topk(np.array([[5, -1, 3, -1]], np.int32), np.array([[7, 0, 7, 0]], np.int32), 3)
+    assert gi.tolist() == [[3, 5, -1]] and gk.tolist() == [[7, 7, 2**31 - 1]]
+
+
+def test_gather_returns_the_rows(oracle):
+    rng = np.random.default_rng(41)
+    buf = rng.standard_normal((50, 24)).astype(np.float16)
+    x = buf[:, :16]  # padded rows
+    ids = np.array([[3, 49, -1], [0, 0, 50]], np.int32)
+    out = oracle.gather(x, ids)
+    assert out.shape == (2, 3, 16)
+    assert np.array_equal(out[0, 0], x[3]) and np.array_equal(out[0, 1], x[49]) and np.array_equal(out[1, 1], x[0])
+    assert not out[0, 2].any() and not out[1, 2].any()
