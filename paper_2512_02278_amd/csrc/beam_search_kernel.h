@@ -25,6 +25,14 @@
 
 #include "row_ops.h"
 
+#ifndef ANN_NT_GRAPH
+#define ANN_NT_GRAPH 0
+#endif
+#if ANN_NT_GRAPH
+#define ANN_GRAPH_LOAD(p) __builtin_nontemporal_load(p)
+#else
+#define ANN_GRAPH_LOAD(p) (*(p))
+#endif
 #ifndef ANN_INSERT_MAX
 #define ANN_INSERT_MAX 8
 #endif
@@ -405,7 +413,7 @@ struct BeamSearch {
                 nb[t] = -1;
                 if (s < nref) {
                     const int pi = (int)(((uint32_t)s * p.degree_inv) >> 20);
-                    nb[t] = __builtin_nontemporal_load(p.graph + (int64_t)parents[pi] * p.degree + (s - pi * p.degree));
+                    nb[t] = ANN_GRAPH_LOAD(p.graph + (int64_t)parents[pi] * p.degree + (s - pi * p.degree));
                 }
             }
             m = 0;
