@@ -21,6 +21,8 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-u
 
 
 EXTRA = os.environ.get("ANN_EXTRA_FLAGS", "").split()  # e.g. -DNAME=VALUE switches while tuning
+# the routing kernels read every matrix result with the vector ALU: keep the accumulators in VGPRs
+PER_FILE = {"route_mfma_u8.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"], "route_mfma.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
 
 
 RESOURCES = {}  # kernel name -> {"VGPRs": .., "ScratchSize": .., "Occupancy": ..}, filled by _compile
@@ -48,7 +50,8 @@ def _resources(stderr: str) -> str:
 
 def _compile(src: str) -> str:
     obj = os.path.join(OBJ, os.path.basename(src) + ".o")
-    r = subprocess.run(["hipcc", *FLAGS, *EXTRA, "-c", src, "-o", obj], capture_output=True, text=True)
+    r = subprocess.run(["hipcc", *FLAGS, *EXTRA, *PER_FILE.get(os.path.basename(src), []), "-c", src, "-o", obj],
+                       capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"hipcc failed on {src}:\n{r.stderr}")
     err = _resources(r.stderr)

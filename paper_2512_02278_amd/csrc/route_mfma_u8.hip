@@ -2,13 +2,14 @@
 //
 // Stage 1 of Fantasy (Sec. 3.2, "Local K-means Assignment") is the one dense
 // contraction on the path: Q (b x d) against the centroids C (d x C), then the
-// nearest clusters per query.  Here: shift both operands by -128 so that they fit
-// int8 (squared L2 does not change; for the inner product the shift only adds a
-// per-centroid and a per-query term), multiply on v_mfma_i32_32x32x32_i8 with exact
-// int32 accumulation, and rank by
-//     L2:  bias_c - 2 q'.c'   with bias_c = sum c'^2          (= key - sum q'^2)
-//     IP:  bias_c -   q'.c'   with bias_c = -128 sum c'       (= key + per-query terms)
-// which orders a query's centroids exactly as (key, cluster index) does.
+// nearest clusters per query.  Here both operands are shifted into int8 and the query
+// is negated on the way, u = 127 - q (byte-wise q ^ 0x7f) and w = c - 128 (c ^ 0x80),
+// multiplied on v_mfma_i32_32x32x32_i8 with exact int32 accumulation (dot = u.w), and
+// ranked by the key without its per-query terms:
+//     L2:  sum (q - c)^2 = sum ((w + 1) + u)^2   ->   bias_c + 2 dot,  bias_c = sum (c - 127)^2
+//     IP:  -q.c = -(127 - u).(w + 128)           ->   bias_c +   dot,  bias_c = -127 sum w
+// which orders a query's centroids exactly as (key, cluster index) does.  Negating the
+// query makes the score a sum, so one shift-add per result forms the packed word below.
 //
 // Tiling.  A = 32 centroids x 32 bytes, B = 32 queries x 32 bytes per instruction;
 // a wavefront keeps 64 queries (two B sets) in registers for the whole kernel and
@@ -51,13 +52,16 @@ __global__ void __launch_bounds__(256) centroid_bias_kernel(const uint8_t* centr
     const uint32_t* row = reinterpret_cast<const uint32_t*>(centroids + (int64_t)c * 128);
     int32_t acc = 0;
     for (int i = 0; i < 32; ++i) {
-        const uint32_t w = row[i] ^ 0x80808080u;
-        if (METRIC == 0)
-            acc = __builtin_amdgcn_sdot4((int)w, (int)w, acc, false);
-        else
+        if (METRIC == 0) {
+            // (c - 127) as int8 is c ^ 0x7f with the sign flipped: its square is the same
+            const uint32_t w1 = row[i] ^ 0x7f7f7f7fu;
+            acc = __builtin_amdgcn_sdot4((int)w1, (int)w1, acc, false);
+        } else {
+            const uint32_t w = row[i] ^ 0x80808080u;
             acc = __builtin_amdgcn_sdot4((int)w, 0x01010101, acc, false);
+        }
     }
-    bias[c] = (METRIC == 0 ? acc : -128 * acc) * 16 + slot;
+    bias[c] = (METRIC == 0 ? acc : -127 * acc) * 16 + slot;
 }
 
 template <int METRIC, int RC>
@@ -82,7 +86,7 @@ __global__ void __launch_bounds__(256) route_mfma_u8_kernel(const uint8_t* __res
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
             b[s][t] = *reinterpret_cast<const v4i*>(queries + q * 128 + (2 * t + half) * 16);
-            b[s][t] ^= (int)0x80808080;
+            b[s][t] ^= (int)0x7f7f7f7f;  // u = 127 - q
         }
     }
     int32_t best_s[NQS][RC], best_i[NQS][RC];
@@ -119,15 +123,22 @@ __global__ void __launch_bounds__(256) route_mfma_u8_kernel(const uint8_t* __res
         v4i bs[4];
 #pragma unroll
         for (int g = 0; g < 4; ++g) bs[g] = btile[ct & 1][2 * g + half];
+        // both query sets are multiplied before either is looked at: the matrix core works on
+        // the second while the vector ALU selects from the first
+        v16i accs[NQS];
 #pragma unroll
         for (int s = 0; s < NQS; ++s) {
-            v16i acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+            accs[s] = v16i{0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
-            for (int t = 0; t < 4; ++t) acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[t], b[s][t], acc, 0, 0, 0);
+            for (int t = 0; t < 4; ++t) accs[s] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[t], b[s][t], accs[s], 0, 0, 0);
+        }
+#pragma unroll
+        for (int s = 0; s < NQS; ++s) {
+            const v16i acc = accs[s];
             // packed[v] = score * 16 + v
             int32_t packed[16];
 #pragma unroll
-            for (int v = 0; v < 16; ++v) packed[v] = bs[v / 4][v % 4] - (METRIC == 0 ? 32 : 16) * acc[v];
+            for (int v = 0; v < 16; ++v) packed[v] = bs[v / 4][v % 4] + (acc[v] << (METRIC == 0 ? 5 : 4));
             int32_t m01 = min(min(packed[0], packed[1]), packed[2]);
             int32_t m02 = min(min(packed[3], packed[4]), packed[5]);
             int32_t m03 = min(min(packed[6], packed[7]), packed[8]);
