@@ -119,6 +119,8 @@ int ann_search_counters(ann_index_t* handle, const void* queries, int64_t nq, in
  * The routing step alone (routed indices only): for each query the route_c nearest
  * clusters under (key(query, centroid), cluster index), ascending.
  *   out_clusters  DEVICE, nq*route_c int32
+ * Small batches split the centroids over more workgroups and use a stream-ordered scratch of
+ * at most nq*64*route_c uint64.
  */
 int ann_route(ann_index_t* handle, const void* queries, int64_t nq, int32_t* out_clusters, void* stream);
 

@@ -228,9 +228,18 @@ extern "C" int ann_route(ann_index_t* h, const void* queries, int64_t nq, int32_
     if (!queries || !out_clusters) return fail(ANN_EINVAL, "ann_route: null argument");
     if (!aligned16(queries)) return fail(ANN_EINVAL, "ann_route: queries not 16-byte aligned");
     if (h->centroid_bias) {
+        hipStream_t st = static_cast<hipStream_t>(stream);
+        const int slices = route_mfma_u8_slices(h->d.n_clusters, nq);
+        uint64_t* partial = nullptr;
+        if (slices > 1) {
+            const hipError_t e = hipMallocAsync(reinterpret_cast<void**>(&partial),
+                                                sizeof(uint64_t) * (size_t)nq * slices * h->d.route_c, st);
+            if (e != hipSuccess) return fail(ANN_ENOMEM, "ann_route: scratch allocation failed: %s", hipGetErrorString(e));
+        }
         const hipError_t e = launch_route_mfma_u8(h->d.metric, h->d.route_c, static_cast<const uint8_t*>(h->d.centroids),
                                                   h->centroid_bias, h->d.n_clusters, static_cast<const uint8_t*>(queries),
-                                                  nq, out_clusters, static_cast<hipStream_t>(stream));
+                                                  nq, out_clusters, partial, slices, st);
+        if (partial) (void)hipFreeAsync(partial, st);
         if (e != hipSuccess) return fail(ANN_EHIP, "ann_route: launch failed: %s", hipGetErrorString(e));
         return ANN_OK;
     }

@@ -14,8 +14,13 @@ inline int route_mfma_u8_padded(int n_clusters) { return (n_clusters + 31) / 32 
 hipError_t launch_centroid_bias_u8(int metric, const uint8_t* centroids, int n_clusters, int32_t* bias,
                                    hipStream_t stream);
 
+// Slices to cut the centroid range into for a batch of nq queries (1 for large batches).
+int route_mfma_u8_slices(int n_clusters, int64_t nq);
+
 // out[q][0..route_c): the nearest clusters of query q under (key, cluster index), ascending.
+// slices > 1 needs `partial`: DEVICE scratch of nq * slices * route_c uint64.
 hipError_t launch_route_mfma_u8(int metric, int route_c, const uint8_t* centroids, const int32_t* bias, int n_clusters,
-                                const uint8_t* queries, int64_t nq, int32_t* out, hipStream_t stream);
+                                const uint8_t* queries, int64_t nq, int32_t* out, uint64_t* partial, int slices,
+                                hipStream_t stream);
 
 }  // namespace ann

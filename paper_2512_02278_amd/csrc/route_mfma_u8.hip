@@ -68,7 +68,11 @@ template <int METRIC, int RC>
 __global__ void __launch_bounds__(256) route_mfma_u8_kernel(const uint8_t* __restrict__ centroids,
                                                             const int32_t* __restrict__ bias, int n_clusters,
                                                             const uint8_t* __restrict__ queries, int64_t nq,
-                                                            int32_t* __restrict__ out) {
+                                                            int32_t* __restrict__ out, uint64_t* __restrict__ partial,
+                                                            int tiles_per_slice) {
+    // blockIdx.y = slice of the centroid tiles this workgroup walks.  With one slice the final
+    // clusters go to `out`; with several, each slice writes its best (score, cluster) words to
+    // partial[q][slice][RC] and route_merge_kernel picks the overall best.
     constexpr int NQS = 2;  // query sets of 32 per wavefront
     __shared__ uint64_t pool[4][NQS * 32][2][RC];
     __shared__ v4i atile[2][8 * 32];  // [piece 0..7][row 0..31] 16-byte units of one centroid tile
@@ -100,17 +104,19 @@ __global__ void __launch_bounds__(256) route_mfma_u8_kernel(const uint8_t* __res
 
     // thread x fetches piece x % 8 of tile row x / 8 (eight threads read one 128-byte row)
     const int ld_row = threadIdx.x >> 3, ld_piece = threadIdx.x & 7;
-    const int n_tiles = (n_clusters + 31) / 32;
+    const int all_tiles = (n_clusters + 31) / 32;
+    const int tile0 = blockIdx.y * tiles_per_slice;
+    const int n_tiles = min(all_tiles, tile0 + tiles_per_slice);
     auto fetch = [&](int ct) {
         int r = ct * 32 + ld_row;
         if (r >= n_clusters) r = n_clusters - 1;
         return *reinterpret_cast<const v4i*>(centroids + (int64_t)r * 128 + ld_piece * 16) ^ (int)0x80808080;
     };
     const v4i* bias4 = reinterpret_cast<const v4i*>(bias);
-    atile[0][ld_piece * 32 + ld_row] = fetch(0);
-    if (threadIdx.x < 8) btile[0][threadIdx.x] = bias4[threadIdx.x];
+    atile[tile0 & 1][ld_piece * 32 + ld_row] = fetch(tile0);
+    if (threadIdx.x < 8) btile[tile0 & 1][threadIdx.x] = bias4[tile0 * 8 + threadIdx.x];
     __syncthreads();
-    for (int ct = 0; ct < n_tiles; ++ct) {
+    for (int ct = tile0; ct < n_tiles; ++ct) {
         v4i next, next_bias;
         if (ct + 1 < n_tiles) {
             next = fetch(ct + 1);
@@ -197,26 +203,79 @@ __global__ void __launch_bounds__(256) route_mfma_u8_kernel(const uint8_t* __res
             const uint64_t x = ia < RC ? pool[wave][lane][0][ia] : ~0ull;
             const uint64_t y = ib < RC ? pool[wave][lane][1][ib] : ~0ull;
             const bool take_x = x < y;
-            out[q * RC + r] = (int32_t)(uint32_t)(take_x ? x : y);
+            if (gridDim.y == 1)
+                out[q * RC + r] = (int32_t)(uint32_t)(take_x ? x : y);
+            else
+                partial[(q * gridDim.y + blockIdx.y) * RC + r] = take_x ? x : y;
             ia += take_x ? 1 : 0;
             ib += take_x ? 0 : 1;
         }
     }
 }
 
+// One thread per query: the RC smallest of its slices' words (each slice's list is ascending).
+template <int RC>
+__global__ void __launch_bounds__(256) route_merge_kernel(const uint64_t* __restrict__ partial, int slices, int64_t nq,
+                                                          int32_t* __restrict__ out) {
+    const int64_t q = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (q >= nq) return;
+    uint64_t best[RC];
+#pragma unroll
+    for (int r = 0; r < RC; ++r) best[r] = ~0ull;
+    for (int i = 0; i < slices * RC; ++i) {
+        uint64_t c = partial[q * slices * RC + i];
+#pragma unroll
+        for (int r = 0; r < RC; ++r) {
+            const uint64_t lo = c < best[r] ? c : best[r];
+            c = c < best[r] ? best[r] : c;
+            best[r] = lo;
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < RC; ++r) out[q * RC + r] = (int32_t)(uint32_t)best[r];
+}
+
 template <int METRIC>
 static hipError_t launch_rc(int rc, const uint8_t* centroids, const int32_t* bias, int n_clusters,
-                            const uint8_t* queries, int64_t nq, int32_t* out, hipStream_t stream) {
-    const dim3 grid((unsigned)((nq + 255) / 256)), block(256);
+                            const uint8_t* queries, int64_t nq, int32_t* out, uint64_t* partial, int slices,
+                            hipStream_t stream) {
+    const int all_tiles = (n_clusters + 31) / 32;
+    const int tiles_per_slice = (all_tiles + slices - 1) / slices;
+    slices = (all_tiles + tiles_per_slice - 1) / tiles_per_slice;  // no slice may start beyond the last tile
+    const dim3 grid((unsigned)((nq + 255) / 256), (unsigned)slices), block(256), mgrid((unsigned)((nq + 255) / 256));
     switch (rc) {
-        case 1: hipLaunchKernelGGL((route_mfma_u8_kernel<METRIC, 1>), grid, block, 0, stream, centroids, bias, n_clusters, queries, nq, out); break;
-        case 2: hipLaunchKernelGGL((route_mfma_u8_kernel<METRIC, 2>), grid, block, 0, stream, centroids, bias, n_clusters, queries, nq, out); break;
-        case 3: hipLaunchKernelGGL((route_mfma_u8_kernel<METRIC, 3>), grid, block, 0, stream, centroids, bias, n_clusters, queries, nq, out); break;
-        case 4: hipLaunchKernelGGL((route_mfma_u8_kernel<METRIC, 4>), grid, block, 0, stream, centroids, bias, n_clusters, queries, nq, out); break;
-        case 5: hipLaunchKernelGGL((route_mfma_u8_kernel<METRIC, 5>), grid, block, 0, stream, centroids, bias, n_clusters, queries, nq, out); break;
-        case 6: hipLaunchKernelGGL((route_mfma_u8_kernel<METRIC, 6>), grid, block, 0, stream, centroids, bias, n_clusters, queries, nq, out); break;
-        case 7: hipLaunchKernelGGL((route_mfma_u8_kernel<METRIC, 7>), grid, block, 0, stream, centroids, bias, n_clusters, queries, nq, out); break;
-        case 8: hipLaunchKernelGGL((route_mfma_u8_kernel<METRIC, 8>), grid, block, 0, stream, centroids, bias, n_clusters, queries, nq, out); break;
+        case 1:
+            hipLaunchKernelGGL((route_mfma_u8_kernel<METRIC, 1>), grid, block, 0, stream, centroids, bias, n_clusters, queries, nq, out, partial, tiles_per_slice);
+            if (slices > 1) hipLaunchKernelGGL((route_merge_kernel<1>), mgrid, block, 0, stream, partial, slices, nq, out);
+            break;
+        case 2:
+            hipLaunchKernelGGL((route_mfma_u8_kernel<METRIC, 2>), grid, block, 0, stream, centroids, bias, n_clusters, queries, nq, out, partial, tiles_per_slice);
+            if (slices > 1) hipLaunchKernelGGL((route_merge_kernel<2>), mgrid, block, 0, stream, partial, slices, nq, out);
+            break;
+        case 3:
+            hipLaunchKernelGGL((route_mfma_u8_kernel<METRIC, 3>), grid, block, 0, stream, centroids, bias, n_clusters, queries, nq, out, partial, tiles_per_slice);
+            if (slices > 1) hipLaunchKernelGGL((route_merge_kernel<3>), mgrid, block, 0, stream, partial, slices, nq, out);
+            break;
+        case 4:
+            hipLaunchKernelGGL((route_mfma_u8_kernel<METRIC, 4>), grid, block, 0, stream, centroids, bias, n_clusters, queries, nq, out, partial, tiles_per_slice);
+            if (slices > 1) hipLaunchKernelGGL((route_merge_kernel<4>), mgrid, block, 0, stream, partial, slices, nq, out);
+            break;
+        case 5:
+            hipLaunchKernelGGL((route_mfma_u8_kernel<METRIC, 5>), grid, block, 0, stream, centroids, bias, n_clusters, queries, nq, out, partial, tiles_per_slice);
+            if (slices > 1) hipLaunchKernelGGL((route_merge_kernel<5>), mgrid, block, 0, stream, partial, slices, nq, out);
+            break;
+        case 6:
+            hipLaunchKernelGGL((route_mfma_u8_kernel<METRIC, 6>), grid, block, 0, stream, centroids, bias, n_clusters, queries, nq, out, partial, tiles_per_slice);
+            if (slices > 1) hipLaunchKernelGGL((route_merge_kernel<6>), mgrid, block, 0, stream, partial, slices, nq, out);
+            break;
+        case 7:
+            hipLaunchKernelGGL((route_mfma_u8_kernel<METRIC, 7>), grid, block, 0, stream, centroids, bias, n_clusters, queries, nq, out, partial, tiles_per_slice);
+            if (slices > 1) hipLaunchKernelGGL((route_merge_kernel<7>), mgrid, block, 0, stream, partial, slices, nq, out);
+            break;
+        case 8:
+            hipLaunchKernelGGL((route_mfma_u8_kernel<METRIC, 8>), grid, block, 0, stream, centroids, bias, n_clusters, queries, nq, out, partial, tiles_per_slice);
+            if (slices > 1) hipLaunchKernelGGL((route_merge_kernel<8>), mgrid, block, 0, stream, partial, slices, nq, out);
+            break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
@@ -233,10 +292,22 @@ hipError_t launch_centroid_bias_u8(int metric, const uint8_t* centroids, int n_c
     return hipGetLastError();
 }
 
+int route_mfma_u8_slices(int n_clusters, int64_t nq) {
+    // small batches leave most CUs idle when every workgroup walks all centroids: cut the
+    // centroid range so that about 512 workgroups exist, each with at least 8 tiles
+    const int64_t groups = (nq + 255) / 256;
+    const int all_tiles = (n_clusters + 31) / 32;
+    int64_t s = 512 / groups;
+    if (s > all_tiles / 8) s = all_tiles / 8;
+    if (s > 64) s = 64;
+    return s < 1 ? 1 : (int)s;
+}
+
 hipError_t launch_route_mfma_u8(int metric, int route_c, const uint8_t* centroids, const int32_t* bias, int n_clusters,
-                                const uint8_t* queries, int64_t nq, int32_t* out, hipStream_t stream) {
-    return metric == 0 ? launch_rc<0>(route_c, centroids, bias, n_clusters, queries, nq, out, stream)
-                       : launch_rc<1>(route_c, centroids, bias, n_clusters, queries, nq, out, stream);
+                                const uint8_t* queries, int64_t nq, int32_t* out, uint64_t* partial, int slices,
+                                hipStream_t stream) {
+    return metric == 0 ? launch_rc<0>(route_c, centroids, bias, n_clusters, queries, nq, out, partial, slices, stream)
+                       : launch_rc<1>(route_c, centroids, bias, n_clusters, queries, nq, out, partial, slices, stream);
 }
 
 }  // namespace ann

@@ -289,7 +289,8 @@ def test_float_parity(oracle, torch_cuda, dt, dim, metric, itopk, width, degree,
 @pytest.mark.parametrize("metric", [0, 1])
 @pytest.mark.parametrize("n_clusters,route_c,nq,dim", [(300, 4, 100, 128), (32, 1, 1, 128), (1000, 8, 777, 128),
                                                         (5, 5, 64, 128), (4097, 3, 300, 128), (333, 2, 130, 64),
-                                                        (200, 8, 65, 256), (70, 1, 40, 32)])
+                                                        (200, 8, 65, 256), (70, 1, 40, 32),
+                                                        (16640, 2, 300, 128), (16384, 1, 1000, 128), (2049, 3, 5, 128)])
 def test_uint8_matrix_core_routing_is_exact(oracle, torch_cuda, monkeypatch, metric, n_clusters, route_c, nq, dim):
     """uint8 d=128 routing runs on the matrix cores (shifted to int8, exact int32 sums) and must give
     the oracle's clusters in the oracle's order, ties by cluster index included; the plain kernel
