@@ -227,27 +227,24 @@ extern "C" int ann_route(ann_index_t* h, const void* queries, int64_t nq, int32_
     if (nq == 0) return ANN_OK;
     if (!queries || !out_clusters) return fail(ANN_EINVAL, "ann_route: null argument");
     if (!aligned16(queries)) return fail(ANN_EINVAL, "ann_route: queries not 16-byte aligned");
-    if (h->centroid_bias) {
+    if (h->centroid_bias || h->route_bias) {
+        // matrix-core routing; small batches cut the centroid range into slices and merge them
         hipStream_t st = static_cast<hipStream_t>(stream);
-        const int slices = route_mfma_u8_slices(h->d.n_clusters, nq);
+        const int slices = h->centroid_bias ? route_mfma_u8_slices(h->d.n_clusters, nq) : route_mfma_slices(h->d.n_clusters, nq);
         uint64_t* partial = nullptr;
         if (slices > 1) {
             const hipError_t e = hipMallocAsync(reinterpret_cast<void**>(&partial),
                                                 sizeof(uint64_t) * (size_t)nq * slices * h->d.route_c, st);
             if (e != hipSuccess) return fail(ANN_ENOMEM, "ann_route: scratch allocation failed: %s", hipGetErrorString(e));
         }
-        const hipError_t e = launch_route_mfma_u8(h->d.metric, h->d.route_c, static_cast<const uint8_t*>(h->d.centroids),
-                                                  h->centroid_bias, h->d.n_clusters, static_cast<const uint8_t*>(queries),
-                                                  nq, out_clusters, partial, slices, st);
+        const uint8_t* cen = static_cast<const uint8_t*>(h->d.centroids);
+        const uint8_t* qs = static_cast<const uint8_t*>(queries);
+        const hipError_t e =
+            h->centroid_bias ? launch_route_mfma_u8(h->d.metric, h->d.route_c, cen, h->centroid_bias, h->d.n_clusters, qs, nq,
+                                                    out_clusters, partial, slices, st)
+                             : launch_route_mfma(h->d.dtype, h->d.metric, h->d.route_c, cen, h->route_bias, h->d.n_clusters,
+                                                 h->row_bytes, qs, nq, out_clusters, partial, slices, st);
         if (partial) (void)hipFreeAsync(partial, st);
-        if (e != hipSuccess) return fail(ANN_EHIP, "ann_route: launch failed: %s", hipGetErrorString(e));
-        return ANN_OK;
-    }
-    if (h->route_bias) {
-        const hipError_t e = launch_route_mfma(h->d.dtype, h->d.metric, h->d.route_c,
-                                               static_cast<const uint8_t*>(h->d.centroids), h->route_bias, h->d.n_clusters,
-                                               h->row_bytes, static_cast<const uint8_t*>(queries), nq, out_clusters,
-                                               static_cast<hipStream_t>(stream));
         if (e != hipSuccess) return fail(ANN_EHIP, "ann_route: launch failed: %s", hipGetErrorString(e));
         return ANN_OK;
     }

@@ -117,7 +117,10 @@ template <int DT, int METRIC, int RC>
 __global__ void __launch_bounds__(256) route_mfma_kernel(const uint8_t* __restrict__ centroids,
                                                          const void* __restrict__ bias_in, int n_clusters,
                                                          int row_bytes, const uint8_t* __restrict__ queries,
-                                                         int64_t nq, int32_t* __restrict__ out) {
+                                                         int64_t nq, int32_t* __restrict__ out,
+                                                         uint64_t* __restrict__ partial, int pairs_per_slice) {
+    // blockIdx.y = slice of the centroid tile pairs this workgroup walks; with several slices the
+    // best words of a slice go to partial[q][slice][RC] and route_merge_kernel finishes the job
     typedef Mma<DT> M;
     typedef typename M::acc_t acc_t;
     typedef typename M::score_t score_t;
@@ -146,8 +149,9 @@ __global__ void __launch_bounds__(256) route_mfma_kernel(const uint8_t* __restri
         }
 
     const int pieces = row_bytes / 32;  // 16-byte pieces per lane and row
-    const int n_pairs = (n_clusters + 63) / 64;
-    for (int cp = 0; cp < n_pairs; ++cp) {
+    const int all_pairs = (n_clusters + 63) / 64;
+    const int n_pairs = min(all_pairs, (int)(blockIdx.y + 1) * pairs_per_slice);
+    for (int cp = blockIdx.y * pairs_per_slice; cp < n_pairs; ++cp) {
         const uint8_t* arow[2];
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
@@ -222,27 +226,72 @@ __global__ void __launch_bounds__(256) route_mfma_kernel(const uint8_t* __restri
             const uint64_t x = ia < RC ? pool[wave][lane][0][ia] : ~0ull;
             const uint64_t y = ib < RC ? pool[wave][lane][1][ib] : ~0ull;
             const bool take_x = x < y;
-            out[q * RC + r] = (int32_t)(uint32_t)(take_x ? x : y);
+            if (gridDim.y == 1)
+                out[q * RC + r] = (int32_t)(uint32_t)(take_x ? x : y);
+            else
+                partial[(q * gridDim.y + blockIdx.y) * RC + r] = take_x ? x : y;
             ia += take_x ? 1 : 0;
             ib += take_x ? 0 : 1;
         }
     }
 }
 
+// One thread per query: the RC smallest of its slices' words.
+template <int RC>
+__global__ void __launch_bounds__(256) route_merge_kernel(const uint64_t* __restrict__ partial, int slices, int64_t nq,
+                                                          int32_t* __restrict__ out) {
+    const int64_t q = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (q >= nq) return;
+    uint64_t best[RC];
+#pragma unroll
+    for (int r = 0; r < RC; ++r) best[r] = ~0ull;
+    for (int i = 0; i < slices * RC; ++i) {
+        uint64_t c = partial[q * slices * RC + i];
+#pragma unroll
+        for (int r = 0; r < RC; ++r) {
+            const uint64_t lo = c < best[r] ? c : best[r];
+            c = c < best[r] ? best[r] : c;
+            best[r] = lo;
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < RC; ++r) out[q * RC + r] = (int32_t)(uint32_t)best[r];
+}
+
+hipError_t launch_route_merge(int route_c, const uint64_t* partial, int slices, int64_t nq, int32_t* out,
+                              hipStream_t stream) {
+    const dim3 grid((unsigned)((nq + 255) / 256)), block(256);
+#define ANN_RC(N) \
+    case N: hipLaunchKernelGGL((route_merge_kernel<N>), grid, block, 0, stream, partial, slices, nq, out); break;
+    switch (route_c) {
+        ANN_RC(1) ANN_RC(2) ANN_RC(3) ANN_RC(4) ANN_RC(5) ANN_RC(6) ANN_RC(7) ANN_RC(8)
+        default: return hipErrorInvalidValue;
+    }
+#undef ANN_RC
+    return hipGetLastError();
+}
+
+int route_mfma_slices(int n_clusters, int64_t nq) { return route_slices((n_clusters + 63) / 64, 4, nq); }
+
 template <int DT, int METRIC>
 static hipError_t launch_rc(int rc, const uint8_t* centroids, const void* bias, int n_clusters, int row_bytes,
-                            const uint8_t* queries, int64_t nq, int32_t* out, hipStream_t stream) {
-    const dim3 grid((unsigned)((nq + 255) / 256)), block(256);
+                            const uint8_t* queries, int64_t nq, int32_t* out, uint64_t* partial, int slices,
+                            hipStream_t stream) {
+    const int all_pairs = (n_clusters + 63) / 64;
+    const int pairs_per_slice = (all_pairs + slices - 1) / slices;
+    slices = (all_pairs + pairs_per_slice - 1) / pairs_per_slice;  // no slice may start beyond the last pair
+    const dim3 grid((unsigned)((nq + 255) / 256), (unsigned)slices), block(256);
 #define ANN_RC(N)                                                                                                 \
     case N:                                                                                                       \
         hipLaunchKernelGGL((route_mfma_kernel<DT, METRIC, N>), grid, block, 0, stream, centroids, bias, n_clusters, \
-                           row_bytes, queries, nq, out);                                                          \
+                           row_bytes, queries, nq, out, partial, pairs_per_slice);                                \
         break;
     switch (rc) {
         ANN_RC(1) ANN_RC(2) ANN_RC(3) ANN_RC(4) ANN_RC(5) ANN_RC(6) ANN_RC(7) ANN_RC(8)
         default: return hipErrorInvalidValue;
     }
 #undef ANN_RC
+    if (slices > 1) return launch_route_merge(rc, partial, slices, nq, out, stream);
     return hipGetLastError();
 }
 
@@ -274,8 +323,8 @@ hipError_t launch_route_bias(int dtype, int metric, const uint8_t* centroids, in
 
 hipError_t launch_route_mfma(int dtype, int metric, int route_c, const uint8_t* centroids, const void* bias,
                              int n_clusters, int row_bytes, const uint8_t* queries, int64_t nq, int32_t* out,
-                             hipStream_t stream) {
-#define ANN_CALL(D, M) launch_rc<D, M>(route_c, centroids, bias, n_clusters, row_bytes, queries, nq, out, stream)
+                             uint64_t* partial, int slices, hipStream_t stream) {
+#define ANN_CALL(D, M) launch_rc<D, M>(route_c, centroids, bias, n_clusters, row_bytes, queries, nq, out, partial, slices, stream)
     ANN_DISPATCH(ANN_CALL)
 #undef ANN_CALL
 }

@@ -29,6 +29,7 @@
 // beats the worst kept score is looked at value by value.
 #include <hip/hip_runtime.h>
 
+#include "route_mfma.h"
 #include "route_mfma_u8.h"
 
 namespace ann {
@@ -213,28 +214,6 @@ __global__ void __launch_bounds__(256) route_mfma_u8_kernel(const uint8_t* __res
     }
 }
 
-// One thread per query: the RC smallest of its slices' words (each slice's list is ascending).
-template <int RC>
-__global__ void __launch_bounds__(256) route_merge_kernel(const uint64_t* __restrict__ partial, int slices, int64_t nq,
-                                                          int32_t* __restrict__ out) {
-    const int64_t q = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (q >= nq) return;
-    uint64_t best[RC];
-#pragma unroll
-    for (int r = 0; r < RC; ++r) best[r] = ~0ull;
-    for (int i = 0; i < slices * RC; ++i) {
-        uint64_t c = partial[q * slices * RC + i];
-#pragma unroll
-        for (int r = 0; r < RC; ++r) {
-            const uint64_t lo = c < best[r] ? c : best[r];
-            c = c < best[r] ? best[r] : c;
-            best[r] = lo;
-        }
-    }
-#pragma unroll
-    for (int r = 0; r < RC; ++r) out[q * RC + r] = (int32_t)(uint32_t)best[r];
-}
-
 template <int METRIC>
 static hipError_t launch_rc(int rc, const uint8_t* centroids, const int32_t* bias, int n_clusters,
                             const uint8_t* queries, int64_t nq, int32_t* out, uint64_t* partial, int slices,
@@ -242,42 +221,35 @@ static hipError_t launch_rc(int rc, const uint8_t* centroids, const int32_t* bia
     const int all_tiles = (n_clusters + 31) / 32;
     const int tiles_per_slice = (all_tiles + slices - 1) / slices;
     slices = (all_tiles + tiles_per_slice - 1) / tiles_per_slice;  // no slice may start beyond the last tile
-    const dim3 grid((unsigned)((nq + 255) / 256), (unsigned)slices), block(256), mgrid((unsigned)((nq + 255) / 256));
+    const dim3 grid((unsigned)((nq + 255) / 256), (unsigned)slices), block(256);
     switch (rc) {
         case 1:
             hipLaunchKernelGGL((route_mfma_u8_kernel<METRIC, 1>), grid, block, 0, stream, centroids, bias, n_clusters, queries, nq, out, partial, tiles_per_slice);
-            if (slices > 1) hipLaunchKernelGGL((route_merge_kernel<1>), mgrid, block, 0, stream, partial, slices, nq, out);
             break;
         case 2:
             hipLaunchKernelGGL((route_mfma_u8_kernel<METRIC, 2>), grid, block, 0, stream, centroids, bias, n_clusters, queries, nq, out, partial, tiles_per_slice);
-            if (slices > 1) hipLaunchKernelGGL((route_merge_kernel<2>), mgrid, block, 0, stream, partial, slices, nq, out);
             break;
         case 3:
             hipLaunchKernelGGL((route_mfma_u8_kernel<METRIC, 3>), grid, block, 0, stream, centroids, bias, n_clusters, queries, nq, out, partial, tiles_per_slice);
-            if (slices > 1) hipLaunchKernelGGL((route_merge_kernel<3>), mgrid, block, 0, stream, partial, slices, nq, out);
             break;
         case 4:
             hipLaunchKernelGGL((route_mfma_u8_kernel<METRIC, 4>), grid, block, 0, stream, centroids, bias, n_clusters, queries, nq, out, partial, tiles_per_slice);
-            if (slices > 1) hipLaunchKernelGGL((route_merge_kernel<4>), mgrid, block, 0, stream, partial, slices, nq, out);
             break;
         case 5:
             hipLaunchKernelGGL((route_mfma_u8_kernel<METRIC, 5>), grid, block, 0, stream, centroids, bias, n_clusters, queries, nq, out, partial, tiles_per_slice);
-            if (slices > 1) hipLaunchKernelGGL((route_merge_kernel<5>), mgrid, block, 0, stream, partial, slices, nq, out);
             break;
         case 6:
             hipLaunchKernelGGL((route_mfma_u8_kernel<METRIC, 6>), grid, block, 0, stream, centroids, bias, n_clusters, queries, nq, out, partial, tiles_per_slice);
-            if (slices > 1) hipLaunchKernelGGL((route_merge_kernel<6>), mgrid, block, 0, stream, partial, slices, nq, out);
             break;
         case 7:
             hipLaunchKernelGGL((route_mfma_u8_kernel<METRIC, 7>), grid, block, 0, stream, centroids, bias, n_clusters, queries, nq, out, partial, tiles_per_slice);
-            if (slices > 1) hipLaunchKernelGGL((route_merge_kernel<7>), mgrid, block, 0, stream, partial, slices, nq, out);
             break;
         case 8:
             hipLaunchKernelGGL((route_mfma_u8_kernel<METRIC, 8>), grid, block, 0, stream, centroids, bias, n_clusters, queries, nq, out, partial, tiles_per_slice);
-            if (slices > 1) hipLaunchKernelGGL((route_merge_kernel<8>), mgrid, block, 0, stream, partial, slices, nq, out);
             break;
         default: return hipErrorInvalidValue;
     }
+    if (slices > 1) return launch_route_merge(rc, partial, slices, nq, out, stream);
     return hipGetLastError();
 }
 
@@ -292,16 +264,7 @@ hipError_t launch_centroid_bias_u8(int metric, const uint8_t* centroids, int n_c
     return hipGetLastError();
 }
 
-int route_mfma_u8_slices(int n_clusters, int64_t nq) {
-    // small batches leave most CUs idle when every workgroup walks all centroids: cut the
-    // centroid range so that about 512 workgroups exist, each with at least 8 tiles
-    const int64_t groups = (nq + 255) / 256;
-    const int all_tiles = (n_clusters + 31) / 32;
-    int64_t s = 512 / groups;
-    if (s > all_tiles / 8) s = all_tiles / 8;
-    if (s > 64) s = 64;
-    return s < 1 ? 1 : (int)s;
-}
+int route_mfma_u8_slices(int n_clusters, int64_t nq) { return route_slices((n_clusters + 31) / 32, 8, nq); }
 
 hipError_t launch_route_mfma_u8(int metric, int route_c, const uint8_t* centroids, const int32_t* bias, int n_clusters,
                                 const uint8_t* queries, int64_t nq, int32_t* out, uint64_t* partial, int slices,
