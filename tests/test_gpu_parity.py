@@ -427,3 +427,66 @@ def test_merge_topk_matches_oracle(oracle, torch_cuda, per_query, k, is_float):
     torch.cuda.synchronize()
     assert np.array_equal(got_i.cpu().numpy(), want_i)
     assert np.array_equal(got_k.cpu().numpy(), want_k)
+
+
+# ----------------------------------------------------------------------------- two streams
+def test_route_and_search_of_consecutive_batches_on_two_streams(oracle, torch_cuda, tiny):
+    """Stage 1 of batch B can run on one stream while stage 3 of batch A runs on another (the
+    single-GPU shadow of the paper's two-microbatch pipeline); the handle is shared and the
+    answers are those of the plain calls."""
+    from paper_2512_02278_amd import ann
+
+    torch = torch_cuda
+    part, q = tiny
+    dev = "cuda:0"
+    h = ann.ann_index_load(part.vectors.to(dev), part.graph.to(dev), n_entry=32, entry_mode=1, seed=5,
+                           centroids=part.centres.to(dev), cluster_offsets=part.offsets.to(dev), route_c=2)
+    qa, qb = q[:50].to(dev).contiguous(), q[50:].to(dev).contiguous()
+    want_a = ann.ann_search(h, qa, 10, 64, 1, 50)
+    want_b = ann.ann_search(h, qb, 10, 64, 1, 50)
+    torch.cuda.synchronize()
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    routes_a = ann.ann_route(h, qa, stream=s1)
+    s1.synchronize()
+    for _ in range(3):
+        got_a = ann.ann_search(h, qa, 10, 64, 1, 50, routes=routes_a, stream=s2)   # stage 3 of batch A
+        routes_b = ann.ann_route(h, qb, stream=s1)                                 # stage 1 of batch B, concurrently
+        s1.synchronize()
+        got_b = ann.ann_search(h, qb, 10, 64, 1, 50, routes=routes_b, stream=s2)
+        s2.synchronize()
+        for got, want in ((got_a, want_a), (got_b, want_b)):
+            assert torch.equal(got[0], want[0]) and torch.equal(got[1], want[1])
+    ann.ann_free(h)
+
+
+# ----------------------------------------------------------------------------- the bench's workload at full size
+def test_hundred_million_partition_sampled_against_oracle(oracle, torch_cuda):
+    """Config 4 at full size (100M x 128 uint8, 16384 clusters, degree 32) in the launch shape the
+    bench times: one call of 100 000 queries, itopk 192, width 4, routed entries, cluster-grouped
+    execution.  The oracle recomputes the first 300 queries one by one; invariants on all."""
+    from paper_2512_02278_amd import ann, inputs
+
+    torch = torch_cuda
+    part = inputs.sift_like(100_000_000, 16384, device="cuda")
+    inputs.knn_graph_clustered(part, 32)
+    q = inputs.sift_like_queries(part, 100_000)
+    h = ann.ann_index_load(part.vectors, part.graph, n_entry=32, entry_mode=1, seed=20251204, centroids=part.centres,
+                           cluster_offsets=part.offsets, route_c=1)
+    cnt = torch.zeros((100_000, 4), dtype=torch.int32, device="cuda")
+    ids, dists = ann.ann_search(h, q, 10, 192, 4, 200, counters=cnt)
+    torch.cuda.synchronize()
+    ann.ann_free(h)
+    ids_all, d_all = ids.cpu().numpy(), dists.cpu().numpy()
+    assert (np.diff(d_all.astype(np.int64), axis=1) >= 0).all()
+    assert (ids_all >= 0).all() and (ids_all < 100_000_000).all()
+    assert all(len(set(r.tolist())) == 10 for r in ids_all[::997])
+    gt = inputs.ground_truth(part, q[:300], 10)
+    assert inputs.recall(ids[:300], gt) > 0.93
+    sample = q[:300].cpu().numpy()
+    ix = oracle.Index(part.vectors.cpu().numpy(), part.graph.cpu().numpy(), n_entry=32, entry_mode=1, seed=20251204,
+                      centroids=part.centres.cpu().numpy(), cluster_offsets=part.offsets.cpu().numpy(), route_c=1)
+    del part
+    oi, od, oc = oracle.search(ix, sample, 10, 192, 4, 200)
+    assert np.array_equal(ids_all[:300], oi) and np.array_equal(d_all[:300], od)
+    c = cnt[:300].cpu().numpy()
+    assert np.array_equal(c[:, 0], oc["iters"]) and np.array_equal(c[:, 1], oc["n_dist"])  # no row gathered twice
