@@ -30,7 +30,7 @@ HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E, published peak
 WORKLOADS = {
     # name: generator settings and search parameters (benchmark configs)
     "sift100m": dict(kind="sift", n=100_000_000, centres=16384, dim=128, degree=32, nq=1_000_000, k=10, width=4,
-                     max_iters=200, itopk_sweep=(128, 160, 192, 224, 256), sweep=(1_000, 10_000, 100_000, 1_000_000),
+                     max_iters=200, itopk_sweep=(128, 144, 160, 176, 184, 192, 208, 224, 256), sweep=(1_000, 10_000, 100_000, 1_000_000),
                      text="100M x 128 uint8 SIFT-like partition, 16384 centres, degree-32 cluster-restricted kNN graph"),
     "sift1m": dict(kind="sift", n=1_000_000, centres=1000, dim=128, degree=32, nq=10_000, k=10, width=4, max_iters=100,
                    itopk_sweep=(128, 160, 192, 256), sweep=(1_000, 10_000),

@@ -147,9 +147,9 @@ struct BeamSearch {
     // (the nearest cluster, where nearly all ids fall) is kept in registers.
     __device__ __forceinline__ int window_bit(uint32_t id) const {
         const uint32_t rel0 = id - w0_lo;
-        if (__builtin_expect(__all(rel0 < w0_size || n_windows <= 1), 1)) return rel0 < w0_size ? (int)rel0 : -1;
         int bit = rel0 < w0_size ? (int)rel0 : -1;
-        for (int w = 1; w < n_windows; ++w) {
+        if (n_windows > 1 && bit < 0)
+            for (int w = 1; w < n_windows; ++w) {
             const uint32_t rel = id - wtab[3 * w];
             if (rel < wtab[3 * w + 1]) bit = (int)(wtab[3 * w + 2] + rel);
         }
