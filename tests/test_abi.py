@@ -109,3 +109,38 @@ def test_binding_refuses_host_tensors():
     g = torch.zeros((100, 32), dtype=torch.int32)
     with pytest.raises(ValueError):
         ann.ann_index_load(x, g)
+
+
+def test_combine_entry_points_reject_bad_arguments():
+    L = ann.lib()
+    rc, h = load(desc())
+    assert rc == ann.ANN_OK
+    assert L.ann_gather_vectors(h, FAKE, 0, FAKE, None) == ann.ANN_OK          # nothing to do
+    assert L.ann_gather_vectors(h, FAKE, -1, FAKE, None) == ann.ANN_EINVAL
+    assert L.ann_gather_vectors(h, None, 4, FAKE, None) == ann.ANN_EINVAL
+    assert L.ann_gather_vectors(h, FAKE, 4, FAKE + 4, None) == ann.ANN_EINVAL  # misaligned output
+    assert L.ann_gather_vectors(None, FAKE, 4, FAKE, None) == ann.ANN_EINVAL
+    assert L.ann_free(h) == ann.ANN_OK
+
+    def merge(key_dtype=ann.ANN_U8, nq=4, per_query=30, k=10, ids=FAKE, keys=FAKE, oi=FAKE, ok=FAKE):
+        return L.ann_merge_topk(key_dtype, ids, keys, nq, per_query, k, oi, ok, None)
+
+    assert merge(nq=0) == ann.ANN_OK
+    assert merge(key_dtype=9) == ann.ANN_EINVAL
+    assert merge(nq=-2) == ann.ANN_EINVAL
+    assert merge(per_query=0) == ann.ANN_EUNSUPPORTED
+    assert merge(per_query=513) == ann.ANN_EUNSUPPORTED
+    assert merge(k=31) == ann.ANN_EINVAL                 # k above per_query
+    assert merge(k=0) == ann.ANN_EINVAL
+    assert merge(ids=None) == ann.ANN_EINVAL
+    assert merge(ok=None) == ann.ANN_EINVAL
+    assert L.ann_calibration_copy(FAKE, FAKE, 0, None) == ann.ANN_OK
+    assert L.ann_calibration_copy(FAKE, FAKE, 24, None) == ann.ANN_EINVAL      # not a multiple of 16
+    assert L.ann_calibration_copy(None, FAKE, 32, None) == ann.ANN_EINVAL
+
+
+def test_reciprocal_division_used_for_graph_slots_is_exact():
+    """The kernel turns s / degree (s < 1024, degree <= 512) into (s * ceil(2^20 / degree)) >> 20."""
+    for d in range(1, 513):
+        inv = ((1 << 20) + d - 1) // d
+        assert all(((s * inv) >> 20) == s // d for s in range(1024)), d
