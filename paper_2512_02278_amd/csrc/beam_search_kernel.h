@@ -421,9 +421,6 @@ struct BeamSearch {
             for (int t = 0; t < CPL; ++t) filter_into(nb[t], t * 64 + lane < nref, m);
             lds_sync();
             m = score(m);
-#ifdef ANN_DEBUG_KEPT
-            n_resets += (m == 0 ? 1 : 0) + (m <= 8 ? 1 << 8 : 0) + (m <= 16 ? 1 << 16 : 0) + (m <= 64 ? 1 << 24 : 0);
-#endif
             lds_sync();
             merge_all(m);
         }
