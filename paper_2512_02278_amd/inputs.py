@@ -278,10 +278,10 @@ def ground_truth(part: Partition, queries: torch.Tensor, k: int, col_block: int 
 
 
 def recall(found: torch.Tensor, truth: torch.Tensor) -> float:
-    """Mean over queries of |found ∩ truth| / k (ids of -1 never match)."""
+    """Mean over queries of |found ∩ truth| / k (ids of -1 never match; a repeated id counts once)."""
     f = found.to(torch.int64)
     t = truth.to(torch.int64).to(f.device)
-    hit = ((f[:, :, None] == t[:, None, :]) & (f[:, :, None] >= 0)).any(2)
+    hit = ((t[:, :, None] == f[:, None, :]) & (t[:, :, None] >= 0)).any(2)
     return float(hit.float().sum() / (truth.shape[0] * truth.shape[1]))
 
 
