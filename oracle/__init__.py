@@ -2,8 +2,8 @@
 
 Only tests, the smoke check and the bench's cpu_baseline leg may import this
 package; the product (paper_2512_02278_amd) never does.  It wraps
-``beam_search.c`` (plain C, compiled with gcc) through ctypes and takes numpy
-arrays that live in host memory.
+``beam_search.c`` and ``graph_optimize.c`` (plain C, compiled with gcc) through
+ctypes and takes numpy arrays that live in host memory.
 """
 from __future__ import annotations
 
@@ -14,7 +14,7 @@ import subprocess
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_SRC = os.path.join(_HERE, "beam_search.c")
+_SRCS = [os.path.join(_HERE, "beam_search.c"), os.path.join(_HERE, "graph_optimize.c")]
 _LIB = os.path.join(_HERE, "liboracle.so")
 
 DT_U8, DT_F16, DT_F32 = 0, 1, 2
@@ -24,10 +24,10 @@ _NP_OF = {DT_U8: np.uint8, DT_F16: np.float16, DT_F32: np.float32}
 
 
 def build(force: bool = True) -> str:
-    """Compile beam_search.c into liboracle.so next to it (gcc, OpenMP over queries)."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+    """Compile the C sources into liboracle.so next to them (gcc, OpenMP over queries / graph rows)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < max(os.path.getmtime(f) for f in _SRCS):
         subprocess.run(
-            ["gcc", "-O2", "-std=c11", "-fopenmp", "-shared", "-fPIC", "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"],
+            ["gcc", "-O2", "-std=c11", "-fopenmp", "-shared", "-fPIC", "-Wall", "-Wextra", "-o", _LIB, *_SRCS, "-lm"],
             check=True,
         )
     return _LIB
@@ -196,4 +196,58 @@ def gather(vectors, ids):
     _load().oracle_gather(_p(vectors), ctypes.c_int64(vectors.shape[0]), ctypes.c_int32(vectors.shape[1]),
                           ctypes.c_int32(dtype_code(vectors)), ctypes.c_int64(vectors.strides[0]), _p(ids),
                           ctypes.c_int64(ids.size), _p(out))
+    return out
+
+
+def _graph_call(name, *args):
+    fn = getattr(_load(), name)
+    fn.restype = ctypes.c_int
+    if fn(*args) != 0:
+        raise ValueError(f"{name} rejected its arguments")
+
+
+def graph_detours(knn):
+    """c(x, j) for every entry of knn[n, d_in]: two-hop routes of smaller rank (-1 where absent)."""
+    knn = _c(knn, np.int32)
+    n, d_in = knn.shape
+    counts = np.empty((n, d_in), np.int32)
+    _graph_call("oracle_graph_detours", _p(knn), ctypes.c_int64(n), ctypes.c_int32(d_in), _p(counts))
+    return counts
+
+
+def graph_prune(knn, d_out):
+    """Rows cut to d_out by ascending (detour count, rank)."""
+    knn = _c(knn, np.int32)
+    n, d_in = knn.shape
+    out = np.empty((n, d_out), np.int32)
+    _graph_call("oracle_graph_prune", _p(knn), ctypes.c_int64(n), ctypes.c_int32(d_in), ctypes.c_int32(d_out), _p(out))
+    return out
+
+
+def graph_reverse(pruned):
+    """Per node, the sources of its first d in-edges in ascending (position in the source's row, source)."""
+    pruned = _c(pruned, np.int32)
+    n, d = pruned.shape
+    out = np.empty((n, d), np.int32)
+    _graph_call("oracle_graph_reverse", _p(pruned), ctypes.c_int64(n), ctypes.c_int32(d), _p(out))
+    return out
+
+
+def graph_merge(pruned, rev):
+    """Forward half, then up to d/2 reverse edges, then the forward tail."""
+    pruned, rev = _c(pruned, np.int32), _c(rev, np.int32)
+    assert pruned.shape == rev.shape
+    n, d = pruned.shape
+    out = np.empty((n, d), np.int32)
+    _graph_call("oracle_graph_merge", _p(pruned), _p(rev), ctypes.c_int64(n), ctypes.c_int32(d), _p(out))
+    return out
+
+
+def graph_optimize(knn, d_out):
+    """knn[n, d_in] (rank order) -> search graph [n, d_out]: prune, reverse, merge."""
+    knn = _c(knn, np.int32)
+    n, d_in = knn.shape
+    out = np.empty((n, d_out), np.int32)
+    _graph_call("oracle_graph_optimize", _p(knn), ctypes.c_int64(n), ctypes.c_int32(d_in), ctypes.c_int32(d_out),
+                _p(out))
     return out

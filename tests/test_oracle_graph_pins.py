@@ -1,0 +1,224 @@
+"""Pins for oracle/graph_optimize.c (kNN graph -> fixed-degree search graph), checked without a GPU.
+
+The paper names the index (Sec. 3.2, Stage 3) but prints no construction and no values, so the
+pins are what the definition and the mathematics fix: two-hop reachability as a boolean matrix
+product, a five-node graph worked by hand, graphs that have no two-hop routes, a closed form,
+a global lexicographic sort for the reverse lists, and the invariants of the merged rows.
+"""
+import numpy as np
+import pytest
+
+
+def random_knn(rng, n, d_in, holes=0.0, junk=0.0):
+    """Rows of distinct ids != x in random order, with some entries made absent."""
+    knn = np.stack([rng.permutation(np.delete(np.arange(n), x))[:d_in] for x in range(n)]).astype(np.int32)
+    if holes:
+        knn[rng.random(knn.shape) < holes] = -1
+    if junk:
+        m = rng.random(knn.shape) < junk
+        knn[m] = rng.choice(np.array([-7, n, n + 3, 2**31 - 1], dtype=np.int64), size=int(m.sum())).astype(np.int32)
+        rows = np.nonzero(rng.random(n) < junk)[0]
+        knn[rows, rng.integers(0, d_in, rows.size)] = rows  # a self loop counts as absent
+    return knn
+
+
+def is_present(knn):
+    n = knn.shape[0]
+    return (knn >= 0) & (knn < n) & (knn != np.arange(n)[:, None])
+
+
+# ----------------------------------------------------------------------------- step 1
+@pytest.mark.parametrize("n,d_in,holes,junk,seed", [(40, 6, 0.0, 0.0, 1), (60, 10, 0.15, 0.0, 2), (33, 12, 0.1, 0.1, 3),
+                                                      (13, 12, 0.0, 0.0, 4)])
+def test_detour_counts_equal_the_squared_adjacency_matrix(oracle, n, d_in, holes, junk, seed):
+    """With A_j[x, z] = 1 iff z is a present entry of row x at a rank below j, the number of routes
+    x -> z -> y over such edges is (A_j A_j)[x, y]; c(x, j) is that entry for y = knn[x][j]."""
+    rng = np.random.default_rng(seed)
+    knn = random_knn(rng, n, d_in, holes, junk)
+    ok = is_present(knn)
+    got = oracle.graph_detours(knn)
+    want = np.full((n, d_in), -1, np.int64)
+    for j in range(d_in):
+        A = np.zeros((n, n), np.int64)
+        for r in range(j):
+            rows = np.nonzero(ok[:, r])[0]
+            A[rows, knn[rows, r]] = 1
+        two_hop = A @ A
+        rows = np.nonzero(ok[:, j])[0]
+        want[rows, j] = two_hop[rows, knn[rows, j]]
+    assert np.array_equal(got, want)
+    assert got.max() > 0  # the case exercises the count, not only zeros
+
+
+HAND_KNN = np.array([[1, 2, 3], [2, 0, 3], [1, 3, 0], [2, 1, 4], [3, 2, 1]], np.int32)
+# Worked by hand from the definition (rank j edge x -> y; routes x -> z -> y with both ranks < j):
+#   row 0: 0->2 via 1 (1 lists 2 first)            -> 1;  0->3 via 2 (2 lists 3 second)   -> 1
+#   row 1: 1->0: 2 lists [1] only                  -> 0;  1->3 via 2 ([1,3])              -> 1
+#   row 2: 2->3: 1 lists [2] only                  -> 0;  2->0 via 1 ([2,0]); 3 has [2,1] -> 1
+#   row 3: 3->1 via 2 ([1])                        -> 1;  3->4: neither 2 nor 1 lists 4   -> 0
+#   row 4: 4->2 via 3 ([2])                        -> 1;  4->1 via 3 ([2,1]) and 2 ([1,3])-> 2
+HAND_COUNTS = np.array([[0, 1, 1], [0, 0, 1], [0, 0, 1], [0, 1, 0], [0, 1, 2]], np.int32)
+HAND_PRUNED_2 = np.array([[1, 2], [2, 0], [1, 3], [2, 4], [3, 2]], np.int32)
+HAND_PRUNED_3 = np.array([[1, 2, 3], [2, 0, 3], [1, 3, 0], [2, 4, 1], [3, 2, 1]], np.int32)
+# in-edges of each node as (position, source), ascending, from HAND_PRUNED_3:
+#   0: (1,1) (2,2)   1: (0,0) (0,2) (2,3) (2,4)   2: (0,1) (0,3) (1,0) (1,4)   3: (0,4) (1,2) (2,0) (2,1)   4: (1,3)
+HAND_REV_3 = np.array([[1, 2, -1], [0, 2, 3], [1, 3, 0], [4, 2, 0], [3, -1, -1]], np.int32)
+# d = 3, h = 1: two forward entries, then one reverse entry not among them, else the forward tail
+HAND_OUT_3 = np.array([[1, 2, 3], [2, 0, 3], [1, 3, 0], [2, 4, 0], [3, 2, 1]], np.int32)
+HAND_REV_2 = np.array([[1, -1], [0, 2], [1, 3], [4, 2], [3, -1]], np.int32)
+
+
+def test_hand_worked_graph(oracle):
+    assert np.array_equal(oracle.graph_detours(HAND_KNN), HAND_COUNTS)
+    assert np.array_equal(oracle.graph_prune(HAND_KNN, 2), HAND_PRUNED_2)   # row 3 keeps rank 2 before rank 1
+    assert np.array_equal(oracle.graph_prune(HAND_KNN, 3), HAND_PRUNED_3)
+    assert np.array_equal(oracle.graph_reverse(HAND_PRUNED_3), HAND_REV_3)  # node 1, 2, 3: four in-edges cut to three
+    assert np.array_equal(oracle.graph_reverse(HAND_PRUNED_2), HAND_REV_2)
+    assert np.array_equal(oracle.graph_merge(HAND_PRUNED_3, HAND_REV_3), HAND_OUT_3)
+    assert np.array_equal(oracle.graph_optimize(HAND_KNN, 3), HAND_OUT_3)
+    assert np.array_equal(oracle.graph_optimize(HAND_KNN, 2), HAND_PRUNED_2)  # every reverse edge is a forward one
+
+
+def test_bipartite_graph_has_no_detours(oracle):
+    """Even nodes list odd nodes only and the reverse: a route x -> z -> y ends on x's own side,
+    where x has no edge, so every count is 0 and pruning keeps the first d_out entries."""
+    rng = np.random.default_rng(5)
+    n, d_in = 50, 9
+    knn = np.empty((n, d_in), np.int32)
+    for x in range(n):
+        other = np.arange(1 - x % 2, n, 2)
+        knn[x] = rng.permutation(other)[:d_in]
+    assert not oracle.graph_detours(knn).any()
+    assert np.array_equal(oracle.graph_prune(knn, 4), knn[:, :4])
+
+
+def test_forward_chain_closed_form(oracle):
+    """knn[x] = [x+1, ..., x+d]: the node x+i+1 lists x+j+1 at rank j-i-1 < j, so every one of the j
+    earlier neighbours gives a route and c(x, j) = j; ids >= n are absent."""
+    n, d = 30, 7
+    knn = (np.arange(n)[:, None] + 1 + np.arange(d)[None, :]).astype(np.int32)
+    want = np.where(knn < n, np.arange(d)[None, :], -1)
+    assert np.array_equal(oracle.graph_detours(knn), want)
+    pruned = oracle.graph_prune(knn, 3)
+    assert np.array_equal(pruned, np.where(knn[:, :3] < n, knn[:, :3], -1))
+    # reversed chain: node y is pointed at by y-1 (position 0), y-2 (position 1), y-3 (position 2)
+    rev = oracle.graph_reverse(pruned)
+    want_rev = np.arange(n)[:, None] - 1 - np.arange(3)[None, :]
+    assert np.array_equal(rev, np.where(want_rev >= 0, want_rev, -1))
+
+
+def test_prune_orders_by_count_then_rank(oracle):
+    rng = np.random.default_rng(6)
+    knn = random_knn(rng, 48, 14, holes=0.1, junk=0.05)
+    counts = oracle.graph_detours(knn)
+    for d_out in (1, 5, 14):
+        pruned = oracle.graph_prune(knn, d_out)
+        for x in range(knn.shape[0]):
+            js = [j for j in range(knn.shape[1]) if counts[x, j] >= 0]
+            js.sort(key=lambda j: (counts[x, j], j))
+            want = [int(knn[x, j]) for j in js[:d_out]]
+            assert pruned[x].tolist() == want + [-1] * (d_out - len(want))
+
+
+# ----------------------------------------------------------------------------- step 3
+@pytest.mark.parametrize("n,d,seed", [(40, 5, 7), (25, 12, 8), (200, 3, 9)])
+def test_reverse_lists_equal_a_global_sort(oracle, n, d, seed):
+    rng = np.random.default_rng(seed)
+    g = random_knn(rng, n, d, holes=0.2, junk=0.05)
+    # skew the in-degrees so that truncation happens
+    hubs = rng.integers(0, 3, (n, 2)).astype(np.int32)
+    g[:, :2] = np.where(hubs == np.arange(n)[:, None], g[:, :2], hubs)
+    g[:, 1] = np.where(g[:, 1] == g[:, 0], -1, g[:, 1])
+    ok = is_present(g)
+    x, k = np.nonzero(ok)
+    y = g[x, k]
+    order = np.lexsort((x, k, y))  # by target, then position, then source
+    want = np.full((n, d), -1, np.int32)
+    fill = np.zeros(n, np.int64)
+    for e in order:
+        if fill[y[e]] < d:
+            want[y[e], fill[y[e]]] = x[e]
+            fill[y[e]] += 1
+    got = oracle.graph_reverse(g)
+    assert np.array_equal(got, want)
+    assert (np.bincount(y, minlength=n) > d).any()  # some list was cut
+
+
+# ----------------------------------------------------------------------------- step 4
+def plane_knn(rng, n, d_in):
+    """Exact kNN of random points in the plane: many edges are mutual, as in a real kNN graph."""
+    pts = rng.random((n, 2))
+    dist = ((pts[:, None, :] - pts[None, :, :]) ** 2).sum(2)
+    np.fill_diagonal(dist, np.inf)
+    return np.argsort(dist, axis=1, kind="stable")[:, :d_in].astype(np.int32)
+
+
+@pytest.mark.parametrize("d,kind", [(1, "random"), (2, "random"), (5, "random"), (8, "random"), (5, "sparse"),
+                                    (4, "plane"), (7, "plane")])
+def test_merged_rows_invariants(oracle, d, kind):
+    rng = np.random.default_rng(10 + d)
+    n = 60
+    if kind == "plane":     # a reverse edge is often a forward edge of the same row as well
+        knn = plane_knn(rng, n, 2 * d + 1)
+    elif kind == "sparse":  # most rows are short, so the forward half has room to spare
+        knn = random_knn(rng, n, 2 * d + 1, holes=0.75)
+    else:
+        knn = random_knn(rng, n, 2 * d + 1, holes=0.1, junk=0.05)
+    pruned = oracle.graph_prune(knn, d)
+    rev = oracle.graph_reverse(pruned)
+    out = oracle.graph_merge(pruned, rev)
+    assert np.array_equal(out, oracle.graph_optimize(knn, d))
+    h = d // 2
+    for x in range(n):
+        row = [v for v in out[x].tolist() if v >= 0]
+        assert out[x].tolist() == row + [-1] * (d - len(row))          # padding only at the end
+        assert len(set(row)) == len(row) and x not in row and all(0 <= v < n for v in row)
+        fwd = [v for v in pruned[x].tolist() if v >= 0]
+        back = [v for v in rev[x].tolist() if v >= 0]
+        head = [v for v in pruned[x, : d - h].tolist() if v >= 0]
+        assert row[: len(head)] == head                                  # the protected forward half
+        assert set(row) <= set(fwd) | set(back)
+        new_back = [v for v in back if v not in head]
+        taken = row[len(head): len(head) + min(h, len(new_back))]
+        assert taken == new_back[:h]                                     # reverse edges in their order
+        tail = [v for v in fwd[len(head):] if v not in taken]
+        assert row[len(head) + len(taken):] == tail[: d - len(head) - len(taken)]
+        if len(fwd) == d:
+            assert len(row) == d                                         # a full forward row stays full
+
+
+def test_merge_without_reverse_edges_is_the_pruned_graph(oracle):
+    rng = np.random.default_rng(20)
+    pruned = random_knn(rng, 30, 6, holes=0.0)
+    assert np.array_equal(oracle.graph_merge(pruned, np.full_like(pruned, -1)), pruned)
+
+
+def test_rejects_bad_arguments(oracle):
+    knn = random_knn(np.random.default_rng(0), 10, 4)
+    with pytest.raises(ValueError):
+        oracle.graph_prune(knn, 5)  # d_out above d_in
+    with pytest.raises(ValueError):
+        oracle.graph_prune(knn, 0)
+
+
+# ----------------------------------------------------------------------------- what it is for
+def test_optimized_graph_searches_better_than_the_truncated_knn_graph(oracle):
+    """What the construction is for: with a list long enough to use the extra reach, the pruned graph
+    with reverse edges finds more of the true neighbours than the plain kNN graph of the same degree
+    (seeded clustered data, entries routed to the two nearest clusters)."""
+    import torch
+
+    from paper_2512_02278_amd import inputs
+
+    part = inputs.sift_like(12000, 12, seed=77, device=torch.device("cpu"))
+    knn = inputs.knn_graph_exact(part, 32).numpy()
+    x = part.vectors.numpy()
+    q = inputs.sift_like_queries(part, 200).numpy()
+    truth, _ = oracle.bruteforce(x, q, 10)
+    recalls = []
+    for graph in (np.ascontiguousarray(knn[:, :16]), oracle.graph_optimize(knn, 16)):
+        ix = oracle.Index(x, graph, n_entry=16, seed=3, entry_mode=1, centroids=part.centres.numpy(),
+                          cluster_offsets=part.offsets.numpy(), route_c=2)
+        ids, _, _ = oracle.search(ix, q, 10, 64, 2, 100)
+        recalls.append(np.mean([len(set(a) & set(b)) / 10 for a, b in zip(ids.tolist(), truth.tolist())]))
+    assert recalls[1] >= recalls[0] + 0.01, recalls
