@@ -167,6 +167,41 @@ int ann_merge_topk(int key_dtype, const int32_t* ids, const void* keys, int64_t 
                    int32_t* out_ids, void* out_keys, void* stream);
 
 /*
+ * Index construction, second half: turns a k-nearest-neighbour graph into the fixed-degree
+ * graph that ann_search walks.  The paper only names the index it searches (Sec. 3.2,
+ * "Stage 3": the CAGRA index); the construction is that index's published graph
+ * optimisation, with ranks in place of distances.  Needs no index handle.
+ *
+ *   knn    DEVICE, n rows of d_in int32: entry j of row x is x's neighbour of rank j (0 = nearest,
+ *          e.g. an exact or approximate kNN list in ascending distance).  An entry outside
+ *          [0, n) or equal to x is "absent" (padding).  The present ids of a row must be
+ *          distinct; with a repeated id the result is unspecified (but no access goes astray).
+ *   n      1 .. 2^31 - 1;  d_in 1 .. 128;  d_out 1 .. min(d_in, 64).
+ *
+ * ann_graph_prune.  Detour count of a present edge x -> y of rank j: the number of ranks
+ * i < j whose node z = knn[x][i] is present and lists y at a rank below j.  Row x of `pruned`
+ * (DEVICE, n*d_out int32) gets the targets of x's present edges in ascending order of
+ * (detour count, rank), cut to d_out and padded with -1.
+ *
+ * ann_graph_optimize.  pruned as above; then node y collects the sources x of the edges
+ * pruned[x][k] == y in ascending order of (k, x), at most d_out of them (its reverse list);
+ * row x of `out_graph` (DEVICE, n*d_out int32) is the first d_out - d_out/2 entries of
+ * pruned[x], then the first d_out/2 entries of x's reverse list that are not among those,
+ * then the remaining entries of pruned[x] that are not in the row yet, cut to d_out and padded
+ * with -1.  The result is deterministic.
+ *   workspace        DEVICE, 256-byte aligned, at least ann_graph_optimize_workspace_bytes(n, d_in,
+ *                    d_out) bytes (about n*d_out*12 + n*12); the caller owns it, its contents
+ *                    afterwards are unspecified, and calls that share a workspace must not overlap.
+ * Both calls only enqueue work on `stream` and never allocate; out-of-range arguments give
+ * ANN_EINVAL / ANN_EUNSUPPORTED before anything is launched.
+ * ann_graph_optimize_workspace_bytes returns a negative error code for arguments out of range.
+ */
+int ann_graph_prune(const int32_t* knn, int64_t n, int d_in, int d_out, int32_t* pruned, void* stream);
+int64_t ann_graph_optimize_workspace_bytes(int64_t n, int d_in, int d_out);
+int ann_graph_optimize(const int32_t* knn, int64_t n, int d_in, int d_out, int32_t* out_graph, void* workspace,
+                       int64_t workspace_bytes, void* stream);
+
+/*
  * Measurement aid, not part of the search: copies `bytes` (a multiple of 16, both
  * pointers DEVICE and 16-byte aligned) with a plain grid-stride kernel named
  * ann_calibration_copy_kernel.  A profiler's HBM byte counters can be calibrated

@@ -22,7 +22,8 @@ ANN_OK, ANN_EINVAL, ANN_EUNSUPPORTED, ANN_ENOMEM, ANN_EHIP = 0, -1, -2, -3, -4
 _DTYPES = {torch.uint8: ANN_U8, torch.float16: ANN_F16, torch.float32: ANN_F32}
 
 EXPORTS = ("ann_index_load", "ann_search", "ann_search_counters", "ann_search_routed", "ann_route", "ann_free",
-           "ann_last_error", "ann_lds_bytes", "ann_calibration_copy", "ann_gather_vectors", "ann_merge_topk")
+           "ann_last_error", "ann_lds_bytes", "ann_calibration_copy", "ann_gather_vectors", "ann_merge_topk",
+           "ann_graph_prune", "ann_graph_optimize", "ann_graph_optimize_workspace_bytes")
 
 
 class ann_index_desc_t(ctypes.Structure):
@@ -74,6 +75,12 @@ def lib() -> ctypes.CDLL:
         L.ann_calibration_copy.restype = ctypes.c_int
         L.ann_lds_bytes.argtypes = [vp, i32, i32]
         L.ann_lds_bytes.restype = ctypes.c_int64
+        L.ann_graph_prune.argtypes = [vp, i64, i32, i32, vp, vp]
+        L.ann_graph_prune.restype = ctypes.c_int
+        L.ann_graph_optimize_workspace_bytes.argtypes = [i64, i32, i32]
+        L.ann_graph_optimize_workspace_bytes.restype = ctypes.c_int64
+        L.ann_graph_optimize.argtypes = [vp, i64, i32, i32, vp, vp, i64, vp]
+        L.ann_graph_optimize.restype = ctypes.c_int
         _lib = L
     return _lib
 
@@ -238,3 +245,49 @@ def ann_merge_topk(ids: torch.Tensor, keys: torch.Tensor, k: int, out_ids: torch
     _check(lib().ann_merge_topk(key_dtype, _dev_ptr(ids, "ids"), _dev_ptr(keys, "keys"), nq, per_query, k,
                                 _dev_ptr(out_ids, "out_ids"), _dev_ptr(out_keys, "out_keys"), _stream(stream)))
     return out_ids, out_keys
+
+
+def _check_knn(knn: torch.Tensor):
+    if knn.dim() != 2 or knn.dtype != torch.int32 or not knn.is_contiguous():
+        raise ValueError("knn must be a contiguous [n, d_in] int32 tensor")
+    return knn.shape
+
+
+def ann_graph_prune(knn: torch.Tensor, d_out: int, pruned: torch.Tensor = None, stream=None) -> torch.Tensor:
+    """knn [n, d_in] int32 in rank order -> [n, d_out]: each row's edges by ascending (detour count, rank)."""
+    n, d_in = _check_knn(knn)
+    if pruned is None:
+        pruned = torch.empty((n, d_out), dtype=torch.int32, device=knn.device)
+    if pruned.dtype != torch.int32 or pruned.numel() != n * d_out or not pruned.is_contiguous():
+        raise ValueError("pruned must be a contiguous int32 tensor of n * d_out elements")
+    _check(lib().ann_graph_prune(_dev_ptr(knn, "knn"), n, d_in, d_out, _dev_ptr(pruned, "pruned"), _stream(stream)))
+    return pruned
+
+
+def ann_graph_optimize_workspace_bytes(n: int, d_in: int, d_out: int) -> int:
+    need = lib().ann_graph_optimize_workspace_bytes(n, d_in, d_out)
+    if need < 0:
+        raise AnnError(int(need), ann_last_error())
+    return int(need)
+
+
+def ann_graph_optimize(knn: torch.Tensor, d_out: int, out_graph: torch.Tensor = None, workspace: torch.Tensor = None,
+                       stream=None) -> torch.Tensor:
+    """knn [n, d_in] int32 in rank order -> search graph [n, d_out] (pruned edges plus reverse edges).
+
+    workspace: a uint8 tensor of at least ann_graph_optimize_workspace_bytes(n, d_in, d_out) bytes; one is
+    allocated (and released when the work is done) if none is given."""
+    n, d_in = _check_knn(knn)
+    if out_graph is None:
+        out_graph = torch.empty((n, d_out), dtype=torch.int32, device=knn.device)
+    if out_graph.dtype != torch.int32 or out_graph.numel() != n * d_out or not out_graph.is_contiguous():
+        raise ValueError("out_graph must be a contiguous int32 tensor of n * d_out elements")
+    if workspace is None:
+        workspace = torch.empty(ann_graph_optimize_workspace_bytes(n, d_in, d_out), dtype=torch.uint8, device=knn.device)
+    if workspace.dtype != torch.uint8 or not workspace.is_contiguous():
+        raise ValueError("workspace must be a contiguous uint8 tensor")
+    _check(lib().ann_graph_optimize(_dev_ptr(knn, "knn"), n, d_in, d_out, _dev_ptr(out_graph, "out_graph"),
+                                    _dev_ptr(workspace, "workspace"), workspace.numel(), _stream(stream)))
+    if stream is not None:
+        workspace.record_stream(stream)
+    return out_graph

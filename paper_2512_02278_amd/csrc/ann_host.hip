@@ -10,6 +10,7 @@
 
 #include "ann.h"
 #include "combine.h"
+#include "graph_build.h"
 #include "route_mfma.h"
 #include "route_mfma_u8.h"
 #include "schedule.h"
@@ -402,6 +403,45 @@ extern "C" int ann_merge_topk(int key_dtype, const int32_t* ids, const void* key
         if (e != hipSuccess) return fail(ANN_EHIP, "ann_merge_topk: launch failed: %s", hipGetErrorString(e));
     }
     return ANN_OK;
+}
+
+namespace {
+
+int check_graph_shape(const char* who, int64_t n, int d_in, int d_out) {
+    if (n < 1 || n > 0x7fffffffLL) return fail(ANN_EINVAL, "%s: n = %lld outside 1..2^31-1", who, (long long)n);
+    if (d_in < 1 || d_out < 1 || d_out > d_in) return fail(ANN_EINVAL, "%s: need 1 <= d_out <= d_in (got %d, %d)", who, d_out, d_in);
+    if (d_in > kMaxKnnDegree || d_out > kMaxGraphDegree)
+        return fail(ANN_EUNSUPPORTED, "%s: d_in = %d above %d or d_out = %d above %d", who, d_in, kMaxKnnDegree, d_out, kMaxGraphDegree);
+    return ANN_OK;
+}
+
+}  // namespace
+
+extern "C" int ann_graph_prune(const int32_t* knn, int64_t n, int d_in, int d_out, int32_t* pruned, void* stream) {
+    if (const int rc = check_graph_shape("ann_graph_prune", n, d_in, d_out)) return rc;
+    if (!knn || !pruned) return fail(ANN_EINVAL, "ann_graph_prune: null argument");
+    const hipError_t e = launch_graph_prune(knn, n, d_in, d_out, pruned, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? ANN_OK : fail(ANN_EHIP, "ann_graph_prune: launch failed: %s", hipGetErrorString(e));
+}
+
+extern "C" int64_t ann_graph_optimize_workspace_bytes(int64_t n, int d_in, int d_out) {
+    if (const int rc = check_graph_shape("ann_graph_optimize_workspace_bytes", n, d_in, d_out)) return rc;
+    return ((n * d_out * 4 + 255) & ~(int64_t)255) + graph_reverse_merge_scratch_bytes(n, d_out);
+}
+
+extern "C" int ann_graph_optimize(const int32_t* knn, int64_t n, int d_in, int d_out, int32_t* out_graph, void* workspace,
+                                  int64_t workspace_bytes, void* stream) {
+    if (const int rc = check_graph_shape("ann_graph_optimize", n, d_in, d_out)) return rc;
+    if (!knn || !out_graph || !workspace) return fail(ANN_EINVAL, "ann_graph_optimize: null argument");
+    if (reinterpret_cast<uintptr_t>(workspace) & 255u) return fail(ANN_EINVAL, "ann_graph_optimize: workspace not 256-byte aligned");
+    const int64_t need = ann_graph_optimize_workspace_bytes(n, d_in, d_out);
+    if (workspace_bytes < need)
+        return fail(ANN_EINVAL, "ann_graph_optimize: workspace of %lld bytes, %lld needed", (long long)workspace_bytes, (long long)need);
+    int32_t* pruned = static_cast<int32_t*>(workspace);
+    char* rest = static_cast<char*>(workspace) + ((n * d_out * 4 + 255) & ~(int64_t)255);
+    hipError_t e = launch_graph_prune(knn, n, d_in, d_out, pruned, static_cast<hipStream_t>(stream));
+    if (e == hipSuccess) e = launch_graph_reverse_merge(pruned, n, d_out, out_graph, rest, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? ANN_OK : fail(ANN_EHIP, "ann_graph_optimize: launch failed: %s", hipGetErrorString(e));
 }
 
 namespace ann {

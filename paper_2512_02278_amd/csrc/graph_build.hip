@@ -1,0 +1,350 @@
+// kNN graph -> fixed-degree search graph.
+//
+// The paper searches "the CAGRA index" (Fantasy Sec. 3.2, stage 3) and leaves its construction
+// to that index's own publication; the steps here are that publication's graph optimisation,
+// with ranks standing in for distances:
+//   1. detour count of an edge x -> y of rank j: the number of earlier neighbours z of x (rank
+//      below j) that list y at a rank below j;
+//   2. a row keeps its d_out edges of smallest (count, rank);
+//   3. reverse edges: node y collects the sources x of its in-edges, ordered by (position of y
+//      in x's pruned row, x), at most d_out of them;
+//   4. merged row: the first d_out - d_out/2 forward edges, then up to d_out/2 reverse edges not
+//      among those, then the remaining forward edges that are not in the row yet.
+// An id outside [0, n) or equal to the row's own node is absent everywhere.
+//
+// One wavefront works on a run of consecutive nodes.  Step 1 is the expensive one: d_in graph
+// rows of d_in ids are read per node (16 KB at d_in = 64), a random gather like the search's
+// own, but with rows that mostly sit in the node's own cluster: runs of consecutive nodes stay
+// on one XCD so that its L2 serves the re-reads.  The ids of x's row go into a small LDS hash
+// (id -> rank); every id of every neighbour's row is looked up there and bumps an LDS counter.
+// Step 3 is a counting sort by target (histogram, scan, scatter of (position, source) words) so
+// that the result does not depend on the order in which the atomics land.
+#include <hip/hip_runtime.h>
+
+#include "graph_build.h"
+#include "wave.h"
+
+namespace ann {
+namespace {
+
+constexpr uint64_t kEmptyRank = ~0ull;
+constexpr int kNodesPerWave = 32;
+constexpr int kScanChunk = 4096;  // elements per workgroup of the scan kernels: 256 threads x 16
+
+__device__ __forceinline__ void wave_lds_sync() { __syncthreads(); }  // one wavefront per workgroup
+
+__device__ __forceinline__ bool is_present(int32_t y, int64_t n, int64_t x) { return y >= 0 && (int64_t)y < n && (int64_t)y != x; }
+
+// Node run of workgroup b: runs are dealt to the 8 XCDs (workgroup b runs on XCD b % 8) so that
+// each XCD walks one contiguous eighth of the ids.
+__device__ __forceinline__ int64_t first_node_of(int64_t b, int64_t runs_per_xcd) {
+    return ((b & 7) * runs_per_xcd + (b >> 3)) * kNodesPerWave;
+}
+
+// ------------------------------------------------------------------------------------- steps 1 + 2
+// R registers per lane: rank j of a row lives in lane j % 64, register j / 64 (d_in <= 64 * R).
+template <int R>
+__global__ void __launch_bounds__(64) graph_prune_kernel(const int32_t* __restrict__ knn, int64_t n, int d_in, int d_out,
+                                                         int32_t* __restrict__ pruned, int64_t runs_per_xcd) {
+    constexpr int kSlots = 256 * R, kBits = R == 1 ? 8 : 9, U = 8;
+    __shared__ uint64_t tab[kSlots];             // (id << 32) | rank of the present ids of x's row
+    __shared__ uint32_t cnt[64 * R];             // detour count per rank
+    __shared__ __align__(16) uint32_t key[64 * R];  // (count << 8) | rank, all ones where absent
+    __shared__ int32_t nbr[64 * R];              // x's row, -1 where absent
+    __shared__ int32_t orow[64];
+    const int lane = lane_id();
+    const int64_t x0 = first_node_of(blockIdx.x, runs_per_xcd);
+    const int64_t x1 = x0 + kNodesPerWave < n ? x0 + kNodesPerWave : n;
+    for (int64_t x = x0; x < x1; ++x) {
+        int32_t mine[R];
+        bool have[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const int j = lane + 64 * r;
+            mine[r] = j < d_in ? knn[x * d_in + j] : -1;
+            have[r] = is_present(mine[r], n, x);
+            nbr[j] = have[r] ? mine[r] : -1;
+            cnt[j] = 0u;
+        }
+        for (int i = lane; i < kSlots; i += 64) tab[i] = kEmptyRank;
+        wave_lds_sync();
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            if (have[r]) {
+                const uint64_t e = ((uint64_t)(uint32_t)mine[r] << 32) | (uint32_t)(lane + 64 * r);
+                uint32_t h = ((uint32_t)mine[r] * 0x9E3779B1u) >> (32 - kBits);
+                for (;;) {  // at most 64 * R of the 256 * R slots are ever taken
+                    const uint64_t old = atomicCAS(reinterpret_cast<unsigned long long*>(&tab[h]), kEmptyRank, e);
+                    if (old == kEmptyRank || (uint32_t)(old >> 32) == (uint32_t)mine[r]) break;
+                    h = (h + 1) & (kSlots - 1);
+                }
+            }
+        }
+        wave_lds_sync();
+
+        // rows of the neighbours at ranks 0 .. d_in-2 (the last one has no edge after it), U rows in flight
+        for (int i0 = 0; i0 < d_in - 1; i0 += U) {
+            int32_t v[U][R];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int i = i0 + u;
+                const int32_t z = i < d_in - 1 ? __builtin_amdgcn_readfirstlane(nbr[i]) : -1;
+#pragma unroll
+                for (int r = 0; r < R; ++r) {
+                    const int rr = lane + 64 * r;
+                    v[u][r] = (z >= 0 && rr < d_in - 1) ? knn[(int64_t)z * d_in + rr] : -1;
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+#pragma unroll
+                for (int r = 0; r < R; ++r) {
+                    const int32_t y = v[u][r];
+                    if (y < 0) continue;
+                    const int later = max(i0 + u, lane + 64 * r);  // both hops must rank below the edge
+                    uint32_t h = ((uint32_t)y * 0x9E3779B1u) >> (32 - kBits);
+                    for (;;) {
+                        const uint64_t e = tab[h];
+                        if ((uint32_t)(e >> 32) == (uint32_t)y) {
+                            const int j = (int)(uint32_t)e;
+                            if (later < j) atomicAdd(&cnt[j], 1u);
+                            break;
+                        }
+                        if (e == kEmptyRank) break;
+                        h = (h + 1) & (kSlots - 1);
+                    }
+                }
+            }
+        }
+        wave_lds_sync();
+
+        // position of every present edge in ascending (count, rank)
+        uint32_t mykey[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const int j = lane + 64 * r;
+            mykey[r] = have[r] ? ((cnt[j] << 8) | (uint32_t)j) : 0xffffffffu;
+            key[j] = mykey[r];
+        }
+        wave_lds_sync();
+        int pos[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) pos[r] = 0;
+        for (int t = 0; t < 16 * R; ++t) {
+            const uint4 k4 = reinterpret_cast<const uint4*>(key)[t];
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+                pos[r] += (k4.x < mykey[r]) + (k4.y < mykey[r]) + (k4.z < mykey[r]) + (k4.w < mykey[r]);
+        }
+        orow[lane] = -1;
+        wave_lds_sync();
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+            if (have[r] && pos[r] < d_out) orow[pos[r]] = mine[r];
+        wave_lds_sync();
+        if (lane < d_out) pruned[x * d_out + lane] = orow[lane];
+        wave_lds_sync();
+    }
+}
+
+// ------------------------------------------------------------------------------------- step 3
+__global__ void __launch_bounds__(256) fill_zero_u32_kernel(uint32_t* p, int64_t n) {
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) p[i] = 0u;
+}
+
+// indeg[y] <- number of edges into y
+__global__ void __launch_bounds__(256) in_degree_kernel(const int32_t* __restrict__ g, int64_t n, int d, uint32_t* indeg) {
+    const int64_t total = n * d;
+    for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (int64_t)gridDim.x * 256) {
+        const int32_t y = g[e];
+        if (is_present(y, n, e / d)) atomicAdd(&indeg[y], 1u);
+    }
+}
+
+// Exclusive scan of indeg[0..n) into off[0..n] (64-bit), in three launches: per-chunk sums, a scan of
+// those by one workgroup, then every chunk scans itself on top of its prefix.
+__global__ void __launch_bounds__(256) chunk_sums_kernel(const uint32_t* __restrict__ deg, int64_t n, int64_t* sums) {
+    __shared__ int64_t part[256];
+    const int t = threadIdx.x;
+    const int64_t base = (int64_t)blockIdx.x * kScanChunk + t * 16;
+    int64_t s = 0;
+    for (int i = 0; i < 16; ++i)
+        if (base + i < n) s += deg[base + i];
+    part[t] = s;
+    __syncthreads();
+    for (int w = 128; w > 0; w >>= 1) {
+        if (t < w) part[t] += part[t + w];
+        __syncthreads();
+    }
+    if (t == 0) sums[blockIdx.x] = part[0];
+}
+
+__global__ void __launch_bounds__(1024) scan_sums_kernel(int64_t* sums, int64_t count) {
+    __shared__ int64_t part[1024];
+    const int t = threadIdx.x;
+    const int64_t per = (count + 1023) / 1024;
+    const int64_t lo = t * per, hi = lo + per < count ? lo + per : count;
+    int64_t s = 0;
+    for (int64_t i = lo; i < hi; ++i) s += sums[i];
+    part[t] = s;
+    __syncthreads();
+    for (int w = 1; w < 1024; w <<= 1) {  // Hillis-Steele inclusive scan of the per-thread sums
+        const int64_t v = t >= w ? part[t - w] : 0;
+        __syncthreads();
+        part[t] += v;
+        __syncthreads();
+    }
+    int64_t run = part[t] - s;
+    for (int64_t i = lo; i < hi; ++i) {
+        const int64_t c = sums[i];
+        sums[i] = run;
+        run += c;
+    }
+}
+
+__global__ void __launch_bounds__(256) offsets_kernel(const uint32_t* __restrict__ deg, int64_t n,
+                                                      const int64_t* __restrict__ sums, int64_t* off) {
+    __shared__ int64_t part[256];
+    const int t = threadIdx.x;
+    const int64_t base = (int64_t)blockIdx.x * kScanChunk + t * 16;
+    int64_t s = 0;
+    for (int i = 0; i < 16; ++i)
+        if (base + i < n) s += deg[base + i];
+    part[t] = s;
+    __syncthreads();
+    for (int w = 1; w < 256; w <<= 1) {
+        const int64_t v = t >= w ? part[t - w] : 0;
+        __syncthreads();
+        part[t] += v;
+        __syncthreads();
+    }
+    int64_t run = sums[blockIdx.x] + part[t] - s;
+    for (int i = 0; i < 16; ++i) {
+        if (base + i < n) {
+            off[base + i] = run;
+            run += deg[base + i];
+            if (base + i == n - 1) off[n] = run;
+        }
+    }
+}
+
+// pairs[off[y] ..) <- (position << 32) | source of every edge into y, in the order the atomics land
+__global__ void __launch_bounds__(256) in_edges_kernel(const int32_t* __restrict__ g, int64_t n, int d,
+                                                       const int64_t* __restrict__ off, uint32_t* cursor, uint64_t* pairs) {
+    const int64_t total = n * d;
+    for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (int64_t)gridDim.x * 256) {
+        const int32_t y = g[e];
+        const int64_t x = e / d;
+        if (is_present(y, n, x)) {
+            const uint32_t slot = atomicAdd(&cursor[y], 1u);
+            pairs[off[y] + slot] = ((uint64_t)(uint32_t)(e - x * d) << 32) | (uint32_t)x;
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------- steps 3 (selection) + 4
+__global__ void __launch_bounds__(64) graph_merge_kernel(const int32_t* __restrict__ pruned, int64_t n, int d,
+                                                         const int64_t* __restrict__ off,
+                                                         const uint64_t* __restrict__ pairs, int32_t* __restrict__ out,
+                                                         int64_t runs_per_xcd) {
+    __shared__ int32_t fwd[64];
+    __shared__ int32_t row[64];
+    const int lane = lane_id();
+    const int h = d / 2, nh = d - h;
+    const int64_t x0 = first_node_of(blockIdx.x, runs_per_xcd);
+    const int64_t x1 = x0 + kNodesPerWave < n ? x0 + kNodesPerWave : n;
+    for (int64_t x = x0; x < x1; ++x) {
+        // the 64 smallest (position, source) words of x's in-edges, ascending: one word per lane
+        uint64_t best[1] = {kInfKey};
+        const int64_t lo = off[x], hi = off[x + 1];
+        for (int64_t c0 = lo; c0 < hi; c0 += 64) {
+            uint64_t v[1] = {c0 + lane < hi ? pairs[c0 + lane] : kInfKey};
+            bitonic_sort<1>(v, lane);
+            // element e of the best so far against element 63 - e of the sorted chunk keeps the 64
+            // smallest of both, as one bitonic run
+            const uint64_t o = xor_lane64<63>(v[0], lane);
+            best[0] = o < best[0] ? o : best[0];
+            bitonic_merge<1>(best, lane);
+        }
+        const int32_t rv = (lane < d && best[0] != kInfKey) ? (int32_t)(uint32_t)best[0] : -1;
+        const int32_t f = lane < d ? pruned[x * d + lane] : -1;
+        const bool fok = is_present(f, n, x);
+        fwd[lane] = fok ? f : -1;
+        const bool head = fok && lane < nh;
+        const uint64_t bh = __ballot(head);
+        const int n_head = __builtin_popcountll(bh);
+        if (head) row[rank_below(bh)] = f;
+        wave_lds_sync();
+        bool member = false;
+        for (int t = 0; t < nh; ++t) member |= fwd[t] == rv;
+        const bool fresh = rv >= 0 && !member;
+        const uint64_t bf = __ballot(fresh);
+        const int rk = rank_below(bf);
+        const int n_fresh = __builtin_popcountll(bf);
+        const int n_take = n_fresh < h ? n_fresh : h;
+        if (fresh && rk < h) row[n_head + rk] = rv;
+        wave_lds_sync();
+        bool dup = false;
+        for (int t = 0; t < n_take; ++t) dup |= row[n_head + t] == f;
+        const bool tail = fok && lane >= nh && !dup;
+        const uint64_t bt = __ballot(tail);
+        const int pos = n_head + n_take + rank_below(bt);
+        if (tail && pos < d) row[pos] = f;
+        const int all = n_head + n_take + __builtin_popcountll(bt);
+        const int len = all < d ? all : d;
+        wave_lds_sync();
+        if (lane < d) out[x * d + lane] = lane < len ? row[lane] : -1;
+        wave_lds_sync();
+    }
+}
+
+unsigned blocks_for(int64_t items) {
+    const int64_t b = (items + 255) / 256;
+    return (unsigned)(b < 65536 ? (b > 0 ? b : 1) : 65536);
+}
+
+int64_t align256(int64_t b) { return (b + 255) & ~(int64_t)255; }
+
+int64_t runs_per_xcd_of(int64_t n) {
+    const int64_t runs = (n + kNodesPerWave - 1) / kNodesPerWave;
+    return (runs + 7) / 8;
+}
+
+}  // namespace
+
+hipError_t launch_graph_prune(const int32_t* knn, int64_t n, int d_in, int d_out, int32_t* pruned, hipStream_t stream) {
+    const int64_t rpx = runs_per_xcd_of(n);
+    if (d_in <= 64)
+        hipLaunchKernelGGL(graph_prune_kernel<1>, dim3((unsigned)(8 * rpx)), dim3(64), 0, stream, knn, n, d_in, d_out, pruned, rpx);
+    else
+        hipLaunchKernelGGL(graph_prune_kernel<2>, dim3((unsigned)(8 * rpx)), dim3(64), 0, stream, knn, n, d_in, d_out, pruned, rpx);
+    return hipGetLastError();
+}
+
+// scratch layout: indeg / cursor (n u32) | off (n + 1 i64) | chunk sums (i64) | pairs (n * d u64)
+int64_t graph_reverse_merge_scratch_bytes(int64_t n, int d) {
+    const int64_t chunks = (n + kScanChunk - 1) / kScanChunk;
+    return align256(n * 4) + align256((n + 1) * 8) + align256(chunks * 8) + align256(n * d * 8);
+}
+
+hipError_t launch_graph_reverse_merge(const int32_t* pruned, int64_t n, int d, int32_t* out, void* scratch,
+                                      hipStream_t stream) {
+    const int64_t chunks = (n + kScanChunk - 1) / kScanChunk;
+    char* base = static_cast<char*>(scratch);
+    uint32_t* indeg = reinterpret_cast<uint32_t*>(base);
+    int64_t* off = reinterpret_cast<int64_t*>(base + align256(n * 4));
+    int64_t* sums = reinterpret_cast<int64_t*>(base + align256(n * 4) + align256((n + 1) * 8));
+    uint64_t* pairs = reinterpret_cast<uint64_t*>(base + align256(n * 4) + align256((n + 1) * 8) + align256(chunks * 8));
+    hipLaunchKernelGGL(fill_zero_u32_kernel, dim3(blocks_for(n)), dim3(256), 0, stream, indeg, n);
+    hipLaunchKernelGGL(in_degree_kernel, dim3(blocks_for(n * d)), dim3(256), 0, stream, pruned, n, d, indeg);
+    hipLaunchKernelGGL(chunk_sums_kernel, dim3((unsigned)chunks), dim3(256), 0, stream, indeg, n, sums);
+    hipLaunchKernelGGL(scan_sums_kernel, dim3(1), dim3(1024), 0, stream, sums, chunks);
+    hipLaunchKernelGGL(offsets_kernel, dim3((unsigned)chunks), dim3(256), 0, stream, indeg, n, sums, off);
+    hipLaunchKernelGGL(fill_zero_u32_kernel, dim3(blocks_for(n)), dim3(256), 0, stream, indeg, n);
+    hipLaunchKernelGGL(in_edges_kernel, dim3(blocks_for(n * d)), dim3(256), 0, stream, pruned, n, d, off, indeg, pairs);
+    const int64_t rpx = runs_per_xcd_of(n);
+    hipLaunchKernelGGL(graph_merge_kernel, dim3((unsigned)(8 * rpx)), dim3(64), 0, stream, pruned, n, d, off, pairs, out, rpx);
+    return hipGetLastError();
+}
+
+}  // namespace ann

@@ -139,6 +139,38 @@ def test_combine_entry_points_reject_bad_arguments():
     assert L.ann_calibration_copy(None, FAKE, 32, None) == ann.ANN_EINVAL
 
 
+def test_graph_construction_rejects_bad_arguments():
+    L = ann.lib()
+
+    def prune(knn=FAKE, n=1000, d_in=64, d_out=32, out=FAKE):
+        return L.ann_graph_prune(knn, n, d_in, d_out, out, None)
+
+    assert prune(knn=None) == ann.ANN_EINVAL
+    assert prune(out=None) == ann.ANN_EINVAL
+    assert prune(n=0) == ann.ANN_EINVAL
+    assert prune(n=2**31) == ann.ANN_EINVAL
+    assert prune(d_out=0) == ann.ANN_EINVAL
+    assert prune(d_in=16, d_out=17) == ann.ANN_EINVAL           # d_out above d_in
+    assert prune(d_in=129, d_out=32) == ann.ANN_EUNSUPPORTED
+    assert prune(d_in=128, d_out=65) == ann.ANN_EUNSUPPORTED
+    need = L.ann_graph_optimize_workspace_bytes(1000, 64, 32)
+    assert need >= 1000 * 32 * 12 + 1000 * 12 and need % 256 == 0
+    assert L.ann_graph_optimize_workspace_bytes(0, 64, 32) == ann.ANN_EINVAL
+    assert L.ann_graph_optimize_workspace_bytes(1000, 200, 32) == ann.ANN_EUNSUPPORTED
+    big = L.ann_graph_optimize_workspace_bytes(100_000_000, 64, 32)
+    assert 38e9 < big < 42e9                                     # pruned rows + (position, source) words + offsets
+
+    def optimize(knn=FAKE, n=1000, d_in=64, d_out=32, out=FAKE, ws=FAKE, ws_bytes=need):
+        return L.ann_graph_optimize(knn, n, d_in, d_out, out, ws, ws_bytes, None)
+
+    assert optimize(knn=None) == ann.ANN_EINVAL
+    assert optimize(ws=None) == ann.ANN_EINVAL
+    assert optimize(ws=FAKE + 16) == ann.ANN_EINVAL             # workspace not 256-byte aligned
+    assert optimize(ws_bytes=need - 1) == ann.ANN_EINVAL
+    assert "needed" in ann.ann_last_error()
+    assert optimize(d_out=65, d_in=128) == ann.ANN_EUNSUPPORTED
+
+
 def test_reciprocal_division_used_for_graph_slots_is_exact():
     """The kernel turns s / degree (s < 1024, degree <= 512) into (s * ceil(2^20 / degree)) >> 20."""
     for d in range(1, 513):
