@@ -12,6 +12,11 @@ recall, bytes per query (algorithmic, from the oracle's counters; actual, from t
 kernel's), the roofline of the beam-search kernel (HBM), a batch-size sweep, and the
 CPU oracle timed on this machine's host cores on a sample of the same batch, which is
 also checked bit for bit against the GPU's answers.
+
+"value" is measured on the workload's own graph (the cluster-restricted kNN graph).
+Where the workload names a longer kNN list to start from, "optimized_graph" adds the
+same measurement on the graph that ann_graph_optimize builds from it at the same
+degree (build time, recall, queries/s, sampled rows checked against the oracle).
 """
 from __future__ import annotations
 
@@ -31,15 +36,18 @@ WORKLOADS = {
     # name: generator settings and search parameters (benchmark configs)
     "sift100m": dict(kind="sift", n=100_000_000, centres=16384, dim=128, degree=32, nq=1_000_000, k=10, width=4,
                      max_iters=200, itopk_sweep=(128, 144, 160, 176, 184, 192, 208, 224, 256), sweep=(1_000, 10_000, 100_000, 1_000_000),
+                     optimize_from=64, opt_itopk_sweep=(96, 104, 112, 120, 128, 144, 160, 184),
                      text="100M x 128 uint8 SIFT-like partition, 16384 centres, degree-32 cluster-restricted kNN graph"),
     "sift1m": dict(kind="sift", n=1_000_000, centres=1000, dim=128, degree=32, nq=10_000, k=10, width=4, max_iters=100,
                    itopk_sweep=(128, 160, 192, 256), sweep=(1_000, 10_000),
+                   optimize_from=64, opt_itopk_sweep=(32, 48, 64, 96, 128),
                    text="1M x 128 uint8 SIFT-like index, 1000 centres, degree-32 cluster-restricted kNN graph"),
     "tiny": dict(kind="sift", n=10_000, centres=100, dim=128, degree=32, nq=100, k=10, width=1, max_iters=50,
                  itopk_sweep=(64,), sweep=(100,), exact_graph=True,
                  text="10k x 128 uint8 SIFT-like index, 100 centres, exact degree-32 kNN graph"),
     "deep10m": dict(kind="unit", dtype="f32", metric="l2", n=10_000_000, centres=4096, dim=96, degree=64, nq=100_000,
                     k=10, width=4, max_iters=150, itopk_sweep=(256,), sweep=(1_000, 10_000, 100_000),
+                    optimize_from=128, opt_itopk_sweep=(64, 96, 128, 192, 256),
                     text="10M x 96 fp32 Deep-like index (unit-norm mixture, 4096 centres, rho 0.5), degree-64 "
                          "cluster-restricted kNN graph, L2"),
     "text20m": dict(kind="unit", dtype="f16", metric="ip", n=20_000_000, centres=8192, dim=768, degree=64, nq=50_000,
@@ -64,6 +72,7 @@ def main() -> int:
     ap.add_argument("--nq", type=int, default=0, help="queries per step (default: the workload's batch)")
     ap.add_argument("--oracle-seconds", type=float, default=15.0, help="wall-clock aim for the CPU oracle sample")
     ap.add_argument("--no-oracle", action="store_true", help="skip the CPU baseline and the sampled parity check")
+    ap.add_argument("--no-optimized-graph", action="store_true", help="skip the optimized-graph measurement")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build covers one GPU's partition; it has no multi-GPU path, run with --gpus 1",
@@ -94,11 +103,56 @@ def main() -> int:
         part = inputs.unit_mixture(w["n"], w["centres"], w["dim"], torch.float32 if dt == "f32" else torch.float16,
                                    inputs.IP if metric == ann.ANN_IP else inputs.L2, seed=SEED, device=dev)
     log(f"vectors generated in {time.time() - t0:.1f} s")
+    d_in = w.get("optimize_from") if not args.no_optimized_graph else None
     if w.get("exact_graph"):
         inputs.knn_graph_exact(part, degree)
     else:
-        inputs.knn_graph_clustered(part, degree, progress=(lambda c, t: log(f"graph: cluster {c}/{t}"),
-                                                           max(1, w["centres"] // 8)))
+        inputs.knn_graph_clustered(part, d_in or degree, progress=(lambda c, t: log(f"graph: cluster {c}/{t}"),
+                                                                   max(1, w["centres"] // 8)))
+    opt = None
+    if d_in:
+        # the kNN lists are built d_in long; their first `degree` columns are the workload's kNN graph
+        knn = part.graph
+        torch.cuda.synchronize()
+        log(f"kNN lists of length {d_in} built in {time.time() - t0:.1f} s")
+        ws = torch.empty(ann.ann_graph_optimize_workspace_bytes(w["n"], d_in, degree), dtype=torch.uint8, device=dev)
+        opt_graph = torch.empty((w["n"], degree), dtype=torch.int32, device=dev)
+
+        def timed(fn):
+            fn()  # warm-up
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            fn()
+            b.record()
+            torch.cuda.synchronize()
+            return a.elapsed_time(b)
+
+        prune_ms = timed(lambda: ann.ann_graph_prune(knn, degree, pruned=opt_graph))
+        build_ms = timed(lambda: ann.ann_graph_optimize(knn, degree, out_graph=opt_graph, workspace=ws))
+        del ws
+        opt = {"from_degree": d_in, "degree": degree,
+               "build_ms": {"graph_prune_kernel": round(prune_ms, 2), "reverse_edges_and_merge": round(build_ms - prune_ms, 2),
+                            "ann_graph_optimize": round(build_ms, 2)}}
+        # d_in rows of d_in ids read per node, the node's own row, the pruned row written
+        prune_bytes = w["n"] * (d_in * d_in * 4 + d_in * 4 + degree * 4)
+        opt["roofline"] = {"bound": "hbm", "kernel": "graph_prune_kernel", "achieved": round(prune_bytes / prune_ms / 1e6, 1),
+                           "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(prune_bytes / prune_ms / 1e6 / HBM_PEAK_GBPS, 4),
+                           "traffic": read_traffic("graph_prune_kernel", args.workload), "kernel_ms": round(prune_ms, 2),
+                           "algorithmic_bytes_per_launch": prune_bytes,
+                           "note": "neighbours' rows are read once per listing node, mostly from L2 (see traffic)"}
+        log(f"graph optimisation {d_in} -> {degree}: prune {prune_ms:.1f} ms, whole build {build_ms:.1f} ms")
+        if not args.no_oracle:
+            from oracle import sampling
+
+            t1 = time.time()
+            rng = np.random.default_rng(SEED)
+            nodes = np.unique(np.concatenate([[0, w["n"] - 1], rng.integers(0, w["n"], 62)]))
+            want = sampling.optimized_rows(knn, nodes, degree)
+            got = opt_graph[torch.as_tensor(nodes, device=dev)].cpu().numpy()
+            opt["parity"] = {"rows_checked": int(nodes.size), "bit_identical": bool(np.array_equal(got, want))}
+            log(f"optimized graph: {opt['parity']} against the oracle in {time.time() - t1:.1f} s")
+        part.graph = knn[:, :degree].contiguous()
+        del knn
     nq_max = max(nq, max(w["sweep"]))
     if w["kind"] == "sift":
         queries = inputs.sift_like_queries(part, nq_max, seed=SEED + 1)
@@ -266,6 +320,37 @@ def main() -> int:
 
     ann.ann_free(h)
 
+    # ------------------------------------------------------------------ the same measurement on the optimized graph
+    if opt is not None:
+        h2 = ann.ann_index_load(part.vectors, opt_graph, metric=metric, n_entry=32, entry_mode=ann.ANN_ENTRY_ROUTED,
+                                seed=SEED + 2, centroids=part.centres, cluster_offsets=part.offsets, route_c=1)
+        opt_recalls, opt_itopk = {}, None
+        for cand in w["opt_itopk_sweep"]:
+            ids, _ = ann.ann_search(h2, queries[:n_gt], k, cand, width, max_iters)
+            torch.cuda.synchronize()
+            opt_recalls[cand] = round(inputs.recall(ids, truth), 4)
+            if opt_recalls[cand] >= 0.95:
+                opt_itopk = cand
+                break
+        opt["recall_target_met"] = opt_itopk is not None
+        opt_itopk = opt_itopk or w["opt_itopk_sweep"][-1]
+        for _ in range(args.warmup):
+            ann.ann_search(h2, q, k, opt_itopk, width, max_iters, out_ids=out_ids, out_dists=out_d)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            ann.ann_search(h2, q, k, opt_itopk, width, max_iters, out_ids=out_ids, out_dists=out_d)
+        torch.cuda.synchronize()
+        opt_wall = (time.perf_counter() - t0) / args.steps
+        ann.ann_search(h2, q, k, opt_itopk, width, max_iters, out_ids=out_ids, out_dists=out_d, counters=counters)
+        torch.cuda.synchronize()
+        ocm = counters.double().mean(0).tolist()
+        opt.update({"itopk": opt_itopk, "recall_by_itopk": opt_recalls, "recall_at_k": round(inputs.recall(out_ids[:n_gt], truth), 4),
+                    "qps": round(nq / opt_wall, 1), "ms_per_step": round(opt_wall * 1e3, 3),
+                    "per_query": {"rounds": round(ocm[0], 2), "rows_gathered": round(ocm[1], 1), "graph_rows": round(ocm[2], 1)}})
+        log(f"optimized graph: itopk {opt_itopk}, recall {opt['recall_at_k']}, {opt['qps']:.3e} q/s, rounds {ocm[0]:.1f}")
+        ann.ann_free(h2)
+
     # a plain copy of known size (1 GiB read, 1 GiB written): calibrates profiler byte counters
     src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).random_(0, 256)
     dst = torch.empty_like(src)
@@ -279,7 +364,7 @@ def main() -> int:
         algo_bq = metrics.algorithmic_bytes_per_query(algo["n_dist"], algo["n_parents"], row_bytes, degree, row_bytes, k)
     else:
         algo_bq = None
-    traffic = read_traffic(args.workload)
+    traffic = read_traffic("beam_search_kernel", args.workload)
     roofline = None
     if algo_bq is not None:
         achieved = algo_bq * nq / (search_ms * 1e-3) / 1e9
@@ -306,16 +391,17 @@ def main() -> int:
         "per_query": {"rounds": round(cm[0], 2), "rows_gathered": round(cm[1], 1), "graph_rows": round(cm[2], 1),
                       "rows_scored_by_oracle": algo["n_dist"]},
         "kernel_ms": {"route_kernel": round(route_ms, 3), "beam_search_kernel": round(search_ms, 3)},
-        "qps_two_streams": round(overlapped_qps, 1), "qps_by_batch": sweep, "parity": parity, "roofline": roofline, "cpu_baseline": cpu_baseline,
+        "qps_two_streams": round(overlapped_qps, 1), "qps_by_batch": sweep, "parity": parity, "optimized_graph": opt,
+        "roofline": roofline, "cpu_baseline": cpu_baseline,
     }
     print(json.dumps(line), flush=True)
     return 0
 
 
-def read_traffic(workload: str):
-    """HBM bytes per launch of the beam-search kernel, from the committed rocprofv3 --pmc
-    summary of this workload (profiles/), or None if none has been recorded."""
-    path = os.path.join(ROOT, "profiles", f"beam_search_kernel_{workload}_pmc.txt")
+def read_traffic(kernel: str, workload: str):
+    """HBM bytes per launch of `kernel`, from the committed rocprofv3 --pmc summary of this
+    workload (profiles/), or None if none has been recorded."""
+    path = os.path.join(ROOT, "profiles", f"{kernel}_{workload}_pmc.txt")
     try:
         for ln in open(path):
             if ln.startswith("traffic_bytes_per_launch"):

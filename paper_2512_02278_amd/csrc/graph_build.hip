@@ -15,7 +15,7 @@
 // One wavefront works on a run of consecutive nodes.  Step 1 is the expensive one: d_in graph
 // rows of d_in ids are read per node (16 KB at d_in = 64), a random gather like the search's
 // own, but with rows that mostly sit in the node's own cluster: runs of consecutive nodes stay
-// on one XCD so that its L2 serves the re-reads.  The ids of x's row go into a small LDS hash
+// on one XCD so that its L2 serves the re-reads.  The ids of x's row go into a small LDS table
 // (id -> rank); every id of every neighbour's row is looked up there and bumps an LDS counter.
 // Step 3 is a counting sort by target (histogram, scan, scatter of (position, source) words) so
 // that the result does not depend on the order in which the atomics land.
@@ -27,8 +27,10 @@
 namespace ann {
 namespace {
 
-constexpr uint64_t kEmptyRank = ~0ull;
-constexpr int kNodesPerWave = 32;
+#ifndef GB_NPW
+#define GB_NPW 32
+#endif
+constexpr int kNodesPerWave = GB_NPW;
 constexpr int kScanChunk = 4096;  // elements per workgroup of the scan kernels: 256 threads x 16
 
 __device__ __forceinline__ void wave_lds_sync() { __syncthreads(); }  // one wavefront per workgroup
@@ -42,15 +44,72 @@ __device__ __forceinline__ int64_t first_node_of(int64_t b, int64_t runs_per_xcd
 }
 
 // ------------------------------------------------------------------------------------- steps 1 + 2
+// id -> rank table of one row: B buckets of four 32-bit ids (one 16-byte LDS read fetches a bucket)
+// plus one byte of rank per slot.  A bucket fills from slot 0 upwards; an id that finds its bucket
+// full goes to the next one.  With 64*R ids in 256*R buckets a full bucket is met by about one
+// lookup in ten thousand, so the lookup is a straight line: one bucket, four compares, and a
+// wave-uniform branch to the rare walk over further buckets.  (A per-lane probing loop would
+// run as long as its slowest lane and cost mostly scalar branch and mask instructions, and the
+// scalar unit is shared by the four SIMDs of a compute unit.)
+constexpr uint32_t kEmptyId = 0xffffffffu;
+
+template <int B>
+__device__ __forceinline__ uint32_t bucket_of(uint32_t id) {
+    return (id * 0x9E3779B1u) >> (32 - __builtin_ctz(B));
+}
+
+// Slot index of `id` in bucket `b`, or -1.
+__device__ __forceinline__ int match_in(const uint4 t, uint32_t id) {
+    return t.x == id ? 0 : t.y == id ? 1 : t.z == id ? 2 : t.w == id ? 3 : -1;
+}
+
+template <int B>
+__device__ __forceinline__ void rank_table_insert(uint32_t* tid, uint8_t* trk, uint32_t id, int rank) {
+    uint32_t b = bucket_of<B>(id);
+    for (;;) {  // ends: the row's ids fill at most a sixteenth of the slots
+        for (int s = 0; s < 4; ++s) {
+            const uint32_t old = atomicCAS(&tid[4 * b + s], kEmptyId, id);
+            if (old == kEmptyId) {
+                trk[4 * b + s] = (uint8_t)rank;
+                return;
+            }
+            if (old == id) return;  // a repeated id keeps the rank that came first
+        }
+        b = (b + 1) & (B - 1);
+    }
+}
+
+// Slot of `id` (4 * bucket + position) or -1.  Called by all lanes; lanes with live == false get -1.
+template <int B>
+__device__ __forceinline__ int rank_table_find(const uint32_t* tid, uint32_t id, bool live) {
+    uint32_t b = bucket_of<B>(id);
+    uint4 t = reinterpret_cast<const uint4*>(tid)[b];
+    int s = match_in(t, id);
+    bool more = live && s < 0 && t.w != kEmptyId;  // bucket full and no match: the id may have moved on
+    while (__ballot(more)) {
+        if (more) {
+            b = (b + 1) & (B - 1);
+            t = reinterpret_cast<const uint4*>(tid)[b];
+            s = match_in(t, id);
+            more = s < 0 && t.w != kEmptyId;
+        }
+    }
+    return (live && s >= 0) ? (int)(4 * b) + s : -1;
+}
+
 // R registers per lane: rank j of a row lives in lane j % 64, register j / 64 (d_in <= 64 * R).
 template <int R>
 __global__ void __launch_bounds__(64) graph_prune_kernel(const int32_t* __restrict__ knn, int64_t n, int d_in, int d_out,
                                                          int32_t* __restrict__ pruned, int64_t runs_per_xcd) {
-    constexpr int kSlots = 256 * R, kBits = R == 1 ? 8 : 9, U = 8;
-    __shared__ uint64_t tab[kSlots];             // (id << 32) | rank of the present ids of x's row
-    __shared__ uint32_t cnt[64 * R];             // detour count per rank
+    #ifndef GB_U
+#define GB_U 8
+#endif
+    constexpr int B = 256 * R, U = GB_U;
+    __shared__ __align__(16) uint32_t tid[4 * B];   // ids of x's row, by bucket
+    __shared__ uint8_t trk[4 * B];                  // their ranks
+    __shared__ uint32_t cnt[64 * R];                // detour count per rank
     __shared__ __align__(16) uint32_t key[64 * R];  // (count << 8) | rank, all ones where absent
-    __shared__ int32_t nbr[64 * R];              // x's row, -1 where absent
+    __shared__ int32_t nbr[64 * R];                 // x's row, -1 where absent
     __shared__ int32_t orow[64];
     const int lane = lane_id();
     const int64_t x0 = first_node_of(blockIdx.x, runs_per_xcd);
@@ -66,20 +125,11 @@ __global__ void __launch_bounds__(64) graph_prune_kernel(const int32_t* __restri
             nbr[j] = have[r] ? mine[r] : -1;
             cnt[j] = 0u;
         }
-        for (int i = lane; i < kSlots; i += 64) tab[i] = kEmptyRank;
+        for (int i = lane; i < B; i += 64) reinterpret_cast<uint4*>(tid)[i] = make_uint4(kEmptyId, kEmptyId, kEmptyId, kEmptyId);
         wave_lds_sync();
 #pragma unroll
-        for (int r = 0; r < R; ++r) {
-            if (have[r]) {
-                const uint64_t e = ((uint64_t)(uint32_t)mine[r] << 32) | (uint32_t)(lane + 64 * r);
-                uint32_t h = ((uint32_t)mine[r] * 0x9E3779B1u) >> (32 - kBits);
-                for (;;) {  // at most 64 * R of the 256 * R slots are ever taken
-                    const uint64_t old = atomicCAS(reinterpret_cast<unsigned long long*>(&tab[h]), kEmptyRank, e);
-                    if (old == kEmptyRank || (uint32_t)(old >> 32) == (uint32_t)mine[r]) break;
-                    h = (h + 1) & (kSlots - 1);
-                }
-            }
-        }
+        for (int r = 0; r < R; ++r)
+            if (have[r]) rank_table_insert<B>(tid, trk, (uint32_t)mine[r], lane + 64 * r);
         wave_lds_sync();
 
         // rows of the neighbours at ranks 0 .. d_in-2 (the last one has no edge after it), U rows in flight
@@ -99,20 +149,20 @@ __global__ void __launch_bounds__(64) graph_prune_kernel(const int32_t* __restri
             for (int u = 0; u < U; ++u) {
 #pragma unroll
                 for (int r = 0; r < R; ++r) {
-                    const int32_t y = v[u][r];
-                    if (y < 0) continue;
-                    const int later = max(i0 + u, lane + 64 * r);  // both hops must rank below the edge
-                    uint32_t h = ((uint32_t)y * 0x9E3779B1u) >> (32 - kBits);
-                    for (;;) {
-                        const uint64_t e = tab[h];
-                        if ((uint32_t)(e >> 32) == (uint32_t)y) {
-                            const int j = (int)(uint32_t)e;
-                            if (later < j) atomicAdd(&cnt[j], 1u);
-                            break;
-                        }
-                        if (e == kEmptyRank) break;
-                        h = (h + 1) & (kSlots - 1);
+#ifdef GB_NO_LOOKUP
+                    if (v[u][r] == 0x7ffffff0) atomicAdd(&cnt[0], 1u);
+#else
+                    const int slot = rank_table_find<B>(tid, (uint32_t)v[u][r], v[u][r] >= 0);
+                    if (slot >= 0) {
+                        const int j = trk[slot];
+                        // both hops must rank below the edge itself
+#ifdef GB_NO_ATOMIC
+                        if (max(i0 + u, lane + 64 * r) < j && j == 200) atomicAdd(&cnt[j], 1u);
+#else
+                        if (max(i0 + u, lane + 64 * r) < j) atomicAdd(&cnt[j], 1u);
+#endif
                     }
+#endif
                 }
             }
         }

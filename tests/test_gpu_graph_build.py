@@ -120,31 +120,6 @@ def test_bad_workspace_is_refused(torch_cuda):
         ann.ann_graph_optimize(knn, 9)
 
 
-def sampled_rows_by_oracle(oracle, torch, knn_t, nodes, d_out):
-    """Rows of the optimized graph for a few nodes of a large graph, computed by the oracle on the subgraph
-    they depend on: the nodes, every node that lists one of them, and those nodes' neighbours.  Ids are
-    relabelled in ascending order (so the order of sources is kept); an id outside the subgraph becomes
-    absent in place, which cannot change a count of the rows that matter, because their own neighbours
-    are all inside."""
-    n, d_in = knn_t.shape
-    nodes_t = torch.as_tensor(nodes, device=knn_t.device, dtype=torch.int32)
-    listing = torch.isin(knn_t, nodes_t).any(dim=1).nonzero().flatten()
-    s1 = torch.unique(torch.cat([listing, nodes_t.long()]))
-    nb = knn_t[s1].flatten().long()
-    nb = nb[(nb >= 0) & (nb < n)]
-    s2 = torch.unique(torch.cat([s1, nb]))                     # sorted ascending
-    sub = knn_t[s2].long()
-    pos = torch.searchsorted(s2, sub.clamp(0, n - 1))
-    pos = pos.clamp(max=s2.numel() - 1)
-    inside = (sub >= 0) & (sub < n) & (s2[pos] == sub)
-    sub = torch.where(inside, pos, torch.full_like(pos, -1)).to(torch.int32).cpu().numpy()
-    out = oracle.graph_optimize(sub, d_out)
-    s2_np = s2.cpu().numpy()
-    where = np.searchsorted(s2_np, np.asarray(nodes))
-    rows = out[where]
-    return np.where(rows >= 0, s2_np[np.clip(rows, 0, None)], -1).astype(np.int32)
-
-
 def test_million_node_graph_sampled(oracle, torch_cuda):
     """The 1M-vector configuration's shape (cluster-restricted kNN, 64 -> 32), checked on sampled rows."""
     torch = torch_cuda
@@ -156,7 +131,9 @@ def test_million_node_graph_sampled(oracle, torch_cuda):
     torch.cuda.synchronize()
     rng = np.random.default_rng(3)
     nodes = np.unique(np.concatenate([[0, 31, 32, 999_999], rng.integers(0, 1_000_000, 60)]))
-    want = sampled_rows_by_oracle(oracle, torch, knn, nodes, 32)
+    from oracle import sampling
+
+    want = sampling.optimized_rows(knn, nodes, 32)
     got = out[torch.as_tensor(nodes, device=out.device)].cpu().numpy()
     assert np.array_equal(got, want)
     # whole-graph properties: full rows, distinct ids, no self loops

@@ -222,3 +222,17 @@ def test_optimized_graph_searches_better_than_the_truncated_knn_graph(oracle):
         ids, _, _ = oracle.search(ix, q, 10, 64, 2, 100)
         recalls.append(np.mean([len(set(a) & set(b)) / 10 for a, b in zip(ids.tolist(), truth.tolist())]))
     assert recalls[1] >= recalls[0] + 0.01, recalls
+
+
+def test_sampled_rows_equal_the_whole_graph_rows(oracle):
+    """oracle/sampling.py cuts out the subgraph a few rows depend on; its rows must be the whole graph's."""
+    import torch
+
+    from oracle import sampling
+    from paper_2512_02278_amd import inputs
+
+    part = inputs.sift_like(6000, 12, seed=5, device=torch.device("cpu"))
+    knn = inputs.knn_graph_clustered(part, 32)
+    full = oracle.graph_optimize(knn.numpy(), 16)
+    nodes = np.unique(np.concatenate([[0, 31, 32, 5999], np.random.default_rng(1).integers(0, 6000, 40)]))
+    assert np.array_equal(sampling.optimized_rows(knn, nodes, 16), full[nodes])
