@@ -16,9 +16,10 @@
 // rows of d_in ids are read per node (16 KB at d_in = 64), a random gather like the search's
 // own, but with rows that mostly sit in the node's own cluster: runs of consecutive nodes stay
 // on one XCD so that its L2 serves the re-reads.  The ids of x's row go into a small LDS table
-// (id -> rank); every id of every neighbour's row is looked up there and bumps an LDS counter.
-// Step 3 is a counting sort by target (histogram, scan, scatter of (position, source) words) so
-// that the result does not depend on the order in which the atomics land.
+// (id -> rank); the ids of every neighbour's row pass a Bloom filter of x's row, and those that
+// survive are looked up in the table and bump an LDS counter.
+// Step 3 is a counting sort by target (histogram, scan, scatter of (position, source) words) followed
+// by a selection per node, so that the result does not depend on the order in which the atomics land.
 #include <hip/hip_runtime.h>
 
 #include "graph_build.h"
@@ -27,10 +28,7 @@
 namespace ann {
 namespace {
 
-#ifndef GB_NPW
-#define GB_NPW 32
-#endif
-constexpr int kNodesPerWave = GB_NPW;
+constexpr int kNodesPerWave = 32;
 constexpr int kScanChunk = 4096;  // elements per workgroup of the scan kernels: 256 threads x 16
 
 __device__ __forceinline__ void wave_lds_sync() { __syncthreads(); }  // one wavefront per workgroup
@@ -46,8 +44,8 @@ __device__ __forceinline__ int64_t first_node_of(int64_t b, int64_t runs_per_xcd
 // ------------------------------------------------------------------------------------- steps 1 + 2
 // id -> rank table of one row: B buckets of four 32-bit ids (one 16-byte LDS read fetches a bucket)
 // plus one byte of rank per slot.  A bucket fills from slot 0 upwards; an id that finds its bucket
-// full goes to the next one.  With 64*R ids in 256*R buckets a full bucket is met by about one
-// lookup in ten thousand, so the lookup is a straight line: one bucket, four compares, and a
+// full goes to the next one.  With 64*R ids in 128*R buckets a full bucket is met by about one
+// lookup in six hundred, so the lookup is a straight line: one bucket, four compares, and a
 // wave-uniform branch to the rare walk over further buckets.  (A per-lane probing loop would
 // run as long as its slowest lane and cost mostly scalar branch and mask instructions, and the
 // scalar unit is shared by the four SIMDs of a compute unit.)
@@ -98,15 +96,18 @@ __device__ __forceinline__ int rank_table_find(const uint32_t* tid, uint32_t id,
 }
 
 // R registers per lane: rank j of a row lives in lane j % 64, register j / 64 (d_in <= 64 * R).
+//
+// Only about one id in ten of a neighbour's row is also in x's row (clustered 128-d data), so the
+// ids first pass a one-hash Bloom filter of x's row (2048 * R bits in LDS, one 4-byte read each);
+// the survivors are queued in LDS with the later of their two ranks and looked up 64 at a time.
 template <int R>
 __global__ void __launch_bounds__(64) graph_prune_kernel(const int32_t* __restrict__ knn, int64_t n, int d_in, int d_out,
                                                          int32_t* __restrict__ pruned, int64_t runs_per_xcd) {
-    #ifndef GB_U
-#define GB_U 8
-#endif
-    constexpr int B = 256 * R, U = GB_U;
+    constexpr int B = 128 * R, U = 8, kBloomBits = 11 + (R > 1), kQueue = 128;
     __shared__ __align__(16) uint32_t tid[4 * B];   // ids of x's row, by bucket
     __shared__ uint8_t trk[4 * B];                  // their ranks
+    __shared__ uint32_t bloom[(1 << kBloomBits) / 32];
+    __shared__ uint64_t queue[kQueue];              // ring of (later rank << 32) | id waiting for a lookup
     __shared__ uint32_t cnt[64 * R];                // detour count per rank
     __shared__ __align__(16) uint32_t key[64 * R];  // (count << 8) | rank, all ones where absent
     __shared__ int32_t nbr[64 * R];                 // x's row, -1 where absent
@@ -114,6 +115,17 @@ __global__ void __launch_bounds__(64) graph_prune_kernel(const int32_t* __restri
     const int lane = lane_id();
     const int64_t x0 = first_node_of(blockIdx.x, runs_per_xcd);
     const int64_t x1 = x0 + kNodesPerWave < n ? x0 + kNodesPerWave : n;
+
+    // looks up queue[head .. head + 64) (the first `live` of them are real) and counts the detours
+    auto drain = [&](int head, int live) {
+        const uint64_t e = queue[(head + lane) & (kQueue - 1)];
+        const int slot = rank_table_find<B>(tid, (uint32_t)e, lane < live);
+        if (slot >= 0) {
+            const int j = trk[slot];
+            if ((int)(e >> 32) < j) atomicAdd(&cnt[j], 1u);  // both hops rank below the edge itself
+        }
+    };
+
     for (int64_t x = x0; x < x1; ++x) {
         int32_t mine[R];
         bool have[R];
@@ -126,13 +138,20 @@ __global__ void __launch_bounds__(64) graph_prune_kernel(const int32_t* __restri
             cnt[j] = 0u;
         }
         for (int i = lane; i < B; i += 64) reinterpret_cast<uint4*>(tid)[i] = make_uint4(kEmptyId, kEmptyId, kEmptyId, kEmptyId);
+        for (int i = lane; i < (1 << kBloomBits) / 32; i += 64) bloom[i] = 0u;
         wave_lds_sync();
 #pragma unroll
-        for (int r = 0; r < R; ++r)
-            if (have[r]) rank_table_insert<B>(tid, trk, (uint32_t)mine[r], lane + 64 * r);
+        for (int r = 0; r < R; ++r) {
+            if (have[r]) {
+                rank_table_insert<B>(tid, trk, (uint32_t)mine[r], lane + 64 * r);
+                const uint32_t hb = ((uint32_t)mine[r] * 0x9E3779B1u) >> (32 - kBloomBits);
+                atomicOr(&bloom[hb >> 5], 1u << (hb & 31));
+            }
+        }
         wave_lds_sync();
 
         // rows of the neighbours at ranks 0 .. d_in-2 (the last one has no edge after it), U rows in flight
+        int head = 0, queued = 0;  // wave-uniform
         for (int i0 = 0; i0 < d_in - 1; i0 += U) {
             int32_t v[U][R];
 #pragma unroll
@@ -149,23 +168,26 @@ __global__ void __launch_bounds__(64) graph_prune_kernel(const int32_t* __restri
             for (int u = 0; u < U; ++u) {
 #pragma unroll
                 for (int r = 0; r < R; ++r) {
-#ifdef GB_NO_LOOKUP
-                    if (v[u][r] == 0x7ffffff0) atomicAdd(&cnt[0], 1u);
-#else
-                    const int slot = rank_table_find<B>(tid, (uint32_t)v[u][r], v[u][r] >= 0);
-                    if (slot >= 0) {
-                        const int j = trk[slot];
-                        // both hops must rank below the edge itself
-#ifdef GB_NO_ATOMIC
-                        if (max(i0 + u, lane + 64 * r) < j && j == 200) atomicAdd(&cnt[j], 1u);
-#else
-                        if (max(i0 + u, lane + 64 * r) < j) atomicAdd(&cnt[j], 1u);
-#endif
+                    const uint32_t y = (uint32_t)v[u][r];
+                    const uint32_t hb = (y * 0x9E3779B1u) >> (32 - kBloomBits);
+                    const bool pass = v[u][r] >= 0 && ((bloom[hb >> 5] >> (hb & 31)) & 1u);
+                    const uint64_t m = __ballot(pass);
+                    if (pass) {
+                        const uint32_t later = (uint32_t)max(i0 + u, lane + 64 * r);
+                        queue[(head + queued + rank_below(m)) & (kQueue - 1)] = ((uint64_t)later << 32) | y;
                     }
-#endif
+                    queued += __builtin_popcountll(m);
+                    if (queued >= 64) {
+                        wave_lds_sync();
+                        drain(head, 64);
+                        head = (head + 64) & (kQueue - 1);
+                        queued -= 64;
+                    }
                 }
             }
         }
+        wave_lds_sync();
+        if (queued > 0) drain(head, queued);
         wave_lds_sync();
 
         // position of every present edge in ascending (count, rank)
@@ -202,12 +224,24 @@ __global__ void __launch_bounds__(256) fill_zero_u32_kernel(uint32_t* p, int64_t
     for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) p[i] = 0u;
 }
 
-// indeg[y] <- number of edges into y
-__global__ void __launch_bounds__(256) in_degree_kernel(const int32_t* __restrict__ g, int64_t n, int d, uint32_t* indeg) {
-    const int64_t total = n * d;
-    for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (int64_t)gridDim.x * 256) {
-        const int32_t y = g[e];
-        if (is_present(y, n, e / d)) atomicAdd(&indeg[y], 1u);
+// Chunk of 256 nodes a workgroup of the two edge kernels works on: like the node runs above, the chunks
+// are dealt so that an XCD walks a contiguous eighth of the ids; the edges of neighbouring nodes point
+// into the same few clusters, and their 8-byte words then meet in one L2 before they are written back.
+__device__ __forceinline__ int64_t chunk_of(int64_t b, int64_t chunks_per_xcd) { return (b & 7) * chunks_per_xcd + (b >> 3); }
+
+// Chunk c covers the 256 nodes from 256 * c on: element t of their rows is
+// node 256 * c + t / d, position t % d, with t / d == (t * d_inv) >> 22 for t < 256 * d, d <= 64
+// (d_inv = ceil(2^22 / d)).
+//
+// indeg[y] <- number of edges into y; slot[e] <- how many of them were counted before edge e
+__global__ void __launch_bounds__(256) in_degree_kernel(const int32_t* __restrict__ g, int64_t n, int d, uint32_t d_inv,
+                                                        uint32_t* indeg, uint32_t* __restrict__ slot, int64_t chunks_per_xcd) {
+    const int64_t xb = chunk_of(blockIdx.x, chunks_per_xcd) * 256;
+    const int rows = n - xb < 256 ? (n > xb ? (int)(n - xb) : 0) : 256;
+    for (int t = threadIdx.x; t < rows * d; t += 256) {
+        const int64_t x = xb + (int)(((uint32_t)t * d_inv) >> 22);
+        const int32_t y = g[xb * d + t];
+        if (is_present(y, n, x)) slot[xb * d + t] = atomicAdd(&indeg[y], 1u);
     }
 }
 
@@ -278,17 +312,17 @@ __global__ void __launch_bounds__(256) offsets_kernel(const uint32_t* __restrict
     }
 }
 
-// pairs[off[y] ..) <- (position << 32) | source of every edge into y, in the order the atomics land
-__global__ void __launch_bounds__(256) in_edges_kernel(const int32_t* __restrict__ g, int64_t n, int d,
-                                                       const int64_t* __restrict__ off, uint32_t* cursor, uint64_t* pairs) {
-    const int64_t total = n * d;
-    for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (int64_t)gridDim.x * 256) {
-        const int32_t y = g[e];
-        const int64_t x = e / d;
-        if (is_present(y, n, x)) {
-            const uint32_t slot = atomicAdd(&cursor[y], 1u);
-            pairs[off[y] + slot] = ((uint64_t)(uint32_t)(e - x * d) << 32) | (uint32_t)x;
-        }
+// pairs[off[y] + slot[e]] <- (position << 32) | source of every edge e into y
+__global__ void __launch_bounds__(256) in_edges_kernel(const int32_t* __restrict__ g, int64_t n, int d, uint32_t d_inv,
+                                                       const int64_t* __restrict__ off, const uint32_t* __restrict__ slot,
+                                                       uint64_t* __restrict__ pairs, int64_t chunks_per_xcd) {
+    const int64_t xb = chunk_of(blockIdx.x, chunks_per_xcd) * 256;
+    const int rows = n - xb < 256 ? (n > xb ? (int)(n - xb) : 0) : 256;
+    for (int t = threadIdx.x; t < rows * d; t += 256) {
+        const int xl = (int)(((uint32_t)t * d_inv) >> 22);
+        const int64_t x = xb + xl;
+        const int32_t y = g[xb * d + t];
+        if (is_present(y, n, x)) pairs[off[y] + slot[xb * d + t]] = ((uint64_t)(uint32_t)(t - xl * d) << 32) | (uint32_t)x;
     }
 }
 
@@ -371,7 +405,7 @@ hipError_t launch_graph_prune(const int32_t* knn, int64_t n, int d_in, int d_out
     return hipGetLastError();
 }
 
-// scratch layout: indeg / cursor (n u32) | off (n + 1 i64) | chunk sums (i64) | pairs (n * d u64)
+// scratch layout: indeg (n u32) | off (n + 1 i64) | chunk sums (i64) | pairs (n * d u64)
 int64_t graph_reverse_merge_scratch_bytes(int64_t n, int d) {
     const int64_t chunks = (n + kScanChunk - 1) / kScanChunk;
     return align256(n * 4) + align256((n + 1) * 8) + align256(chunks * 8) + align256(n * d * 8);
@@ -385,13 +419,17 @@ hipError_t launch_graph_reverse_merge(const int32_t* pruned, int64_t n, int d, i
     int64_t* off = reinterpret_cast<int64_t*>(base + align256(n * 4));
     int64_t* sums = reinterpret_cast<int64_t*>(base + align256(n * 4) + align256((n + 1) * 8));
     uint64_t* pairs = reinterpret_cast<uint64_t*>(base + align256(n * 4) + align256((n + 1) * 8) + align256(chunks * 8));
+    // until the last kernel writes it, `out` holds the slot of every edge within its target's list
+    uint32_t* slot = reinterpret_cast<uint32_t*>(out);
+    const uint32_t d_inv = (uint32_t)(((1u << 22) + d - 1) / d);
+    const int64_t chunks_per_xcd = ((n + 255) / 256 + 7) / 8;
+    const unsigned node_blocks = (unsigned)(8 * chunks_per_xcd);
     hipLaunchKernelGGL(fill_zero_u32_kernel, dim3(blocks_for(n)), dim3(256), 0, stream, indeg, n);
-    hipLaunchKernelGGL(in_degree_kernel, dim3(blocks_for(n * d)), dim3(256), 0, stream, pruned, n, d, indeg);
+    hipLaunchKernelGGL(in_degree_kernel, dim3(node_blocks), dim3(256), 0, stream, pruned, n, d, d_inv, indeg, slot, chunks_per_xcd);
     hipLaunchKernelGGL(chunk_sums_kernel, dim3((unsigned)chunks), dim3(256), 0, stream, indeg, n, sums);
     hipLaunchKernelGGL(scan_sums_kernel, dim3(1), dim3(1024), 0, stream, sums, chunks);
     hipLaunchKernelGGL(offsets_kernel, dim3((unsigned)chunks), dim3(256), 0, stream, indeg, n, sums, off);
-    hipLaunchKernelGGL(fill_zero_u32_kernel, dim3(blocks_for(n)), dim3(256), 0, stream, indeg, n);
-    hipLaunchKernelGGL(in_edges_kernel, dim3(blocks_for(n * d)), dim3(256), 0, stream, pruned, n, d, off, indeg, pairs);
+    hipLaunchKernelGGL(in_edges_kernel, dim3(node_blocks), dim3(256), 0, stream, pruned, n, d, d_inv, off, slot, pairs, chunks_per_xcd);
     const int64_t rpx = runs_per_xcd_of(n);
     hipLaunchKernelGGL(graph_merge_kernel, dim3((unsigned)(8 * rpx)), dim3(64), 0, stream, pruned, n, d, off, pairs, out, rpx);
     return hipGetLastError();

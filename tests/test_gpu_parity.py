@@ -463,12 +463,32 @@ def test_route_and_search_of_consecutive_batches_on_two_streams(oracle, torch_cu
 def test_hundred_million_partition_sampled_against_oracle(oracle, torch_cuda):
     """Config 4 at full size (100M x 128 uint8, 16384 clusters, degree 32) in the launch shape the
     bench times: one call of 100 000 queries, itopk 192, width 4, routed entries, cluster-grouped
-    execution.  The oracle recomputes the first 300 queries one by one; invariants on all."""
+    execution.  The oracle recomputes the first 300 queries one by one; invariants on all.
+    The graph construction runs at the same size first (kNN lists of 64 -> degree 32, as the bench
+    does it): sampled rows against the oracle, and whole-graph invariants."""
+    from oracle import sampling
     from paper_2512_02278_amd import ann, inputs
 
     torch = torch_cuda
-    part = inputs.sift_like(100_000_000, 16384, device="cuda")
-    inputs.knn_graph_clustered(part, 32)
+    n = 100_000_000
+    part = inputs.sift_like(n, 16384, device="cuda")
+    knn = inputs.knn_graph_clustered(part, 64)
+    opt = ann.ann_graph_optimize(knn, 32)
+    torch.cuda.synchronize()
+    nodes = np.unique(np.concatenate([[0, 31, 32, n - 1], np.random.default_rng(7).integers(0, n, 44)]))
+    got = opt[torch.as_tensor(nodes, device="cuda")].cpu().numpy()
+    assert np.array_equal(got, sampling.optimized_rows(knn, nodes, 32))
+    assert int((opt < 0).sum()) == 0 and int((opt >= n).sum()) == 0          # full rows of valid ids
+    for lo in range(0, n, 25_000_000):                                          # distinct, no self loops
+        srt = torch.sort(opt[lo:lo + 25_000_000], dim=1).values
+        assert int((srt[:, 1:] == srt[:, :-1]).sum()) == 0
+        own = torch.arange(lo, min(n, lo + 25_000_000), device="cuda", dtype=torch.int32)[:, None]
+        assert int((opt[lo:lo + 25_000_000] == own).sum()) == 0
+        del srt, own
+    del opt
+    part.graph = knn[:, :32].contiguous()  # the degree-32 kNN graph the search part below uses
+    del knn
+    torch.cuda.empty_cache()
     q = inputs.sift_like_queries(part, 100_000)
     h = ann.ann_index_load(part.vectors, part.graph, n_entry=32, entry_mode=1, seed=20251204, centroids=part.centres,
                            cluster_offsets=part.offsets, route_c=1)
