@@ -47,7 +47,7 @@ WORKLOADS = {
                  text="10k x 128 uint8 SIFT-like index, 100 centres, exact degree-32 kNN graph"),
     "deep10m": dict(kind="unit", dtype="f32", metric="l2", n=10_000_000, centres=4096, dim=96, degree=64, nq=100_000,
                     k=10, width=4, max_iters=150, itopk_sweep=(256,), sweep=(1_000, 10_000, 100_000),
-                    optimize_from=128, opt_itopk_sweep=(64, 96, 128, 192, 256),
+                    optimize_from=128, opt_itopk_sweep=(32, 48, 64, 96, 128, 192, 256),
                     text="10M x 96 fp32 Deep-like index (unit-norm mixture, 4096 centres, rho 0.5), degree-64 "
                          "cluster-restricted kNN graph, L2"),
     "text20m": dict(kind="unit", dtype="f16", metric="ip", n=20_000_000, centres=8192, dim=768, degree=64, nq=50_000,
