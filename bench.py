@@ -351,6 +351,18 @@ def main() -> int:
         log(f"optimized graph: itopk {opt_itopk}, recall {opt['recall_at_k']}, {opt['qps']:.3e} q/s, rounds {ocm[0]:.1f}")
         ann.ann_free(h2)
 
+    # ------------------------------------------------------------------ what random whole-row reads reach on this table
+    hg = ann.ann_index_load(part.vectors, part.graph, metric=metric, n_entry=32)
+    n_rows = int(min(1 << 26, (8 << 30) // row_bytes))
+    rnd = torch.randint(0, w["n"], (n_rows,), dtype=torch.int32, device=dev)
+    sink = torch.zeros(1, dtype=torch.int32, device=dev)
+    ann.ann_calibration_gather(hg, rnd, sink=sink)  # warm-up
+    gather_ms = min(event_ms(lambda: ann.ann_calibration_gather(hg, rnd, sink=sink), 1) for _ in range(5))
+    gather_gbps = n_rows * row_bytes / gather_ms / 1e6
+    log(f"random row gather ({n_rows} rows of {row_bytes} B): {gather_ms:.3f} ms, {gather_gbps:.0f} GB/s")
+    ann.ann_free(hg)
+    del rnd
+
     # a plain copy of known size (1 GiB read, 1 GiB written): calibrates profiler byte counters
     src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).random_(0, 256)
     dst = torch.empty_like(src)
@@ -377,7 +389,12 @@ def main() -> int:
                             "drawn_order is the same kernel with the grouping switched off, where traffic equals "
                             "the algorithmic bytes",
                     "drawn_order": {"kernel_ms": round(ungrouped_ms, 3), "achieved": round(ungrouped, 1),
-                                    "frac": round(ungrouped / HBM_PEAK_GBPS, 4)}}
+                                    "frac": round(ungrouped / HBM_PEAK_GBPS, 4),
+                                    "frac_of_gather_ceiling": round(ungrouped / gather_gbps, 4)},
+                    "gather_ceiling": {"achieved": round(gather_gbps, 1), "unit": "GB/s", "rows": n_rows,
+                                       "note": "ann_calibration_gather: uniformly random whole rows of the same "
+                                               "vector table, nothing else; the practical ceiling for this access "
+                                               "pattern"}}
 
     line = {
         "metric": f"queries/sec at recall@{k}>=0.95 on 1 MI355X", "value": round(qps, 1), "unit": "queries/s",

@@ -209,6 +209,16 @@ int ann_graph_optimize(const int32_t* knn, int64_t n, int d_in, int d_out, int32
  */
 int ann_calibration_copy(void* dst, const void* src, int64_t bytes, void* stream);
 
+/*
+ * Measurement aid, not part of the search: reads the rows of `count` ids (DEVICE, int32, each in
+ * [0, n)) of the index's vector table, 16 bytes per lane, several loads in flight, with a kernel named
+ * ann_calibration_gather_kernel, and xors everything it read into *sink (DEVICE, 4 bytes, which the
+ * caller zeroes).  With uniformly random ids this measures what the memory system delivers for the
+ * search's own access pattern (whole rows at random), the practical ceiling below the HBM peak.
+ * An id outside [0, n) is skipped (nothing is read for it).
+ */
+int ann_calibration_gather(ann_index_t* handle, const int32_t* ids, int64_t count, uint32_t* sink, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

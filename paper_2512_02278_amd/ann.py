@@ -23,7 +23,7 @@ _DTYPES = {torch.uint8: ANN_U8, torch.float16: ANN_F16, torch.float32: ANN_F32}
 
 EXPORTS = ("ann_index_load", "ann_search", "ann_search_counters", "ann_search_routed", "ann_route", "ann_free",
            "ann_last_error", "ann_lds_bytes", "ann_calibration_copy", "ann_gather_vectors", "ann_merge_topk",
-           "ann_graph_prune", "ann_graph_optimize", "ann_graph_optimize_workspace_bytes")
+           "ann_graph_prune", "ann_graph_optimize", "ann_graph_optimize_workspace_bytes", "ann_calibration_gather")
 
 
 class ann_index_desc_t(ctypes.Structure):
@@ -75,6 +75,8 @@ def lib() -> ctypes.CDLL:
         L.ann_calibration_copy.restype = ctypes.c_int
         L.ann_lds_bytes.argtypes = [vp, i32, i32]
         L.ann_lds_bytes.restype = ctypes.c_int64
+        L.ann_calibration_gather.argtypes = [vp, vp, i64, vp, vp]
+        L.ann_calibration_gather.restype = ctypes.c_int
         L.ann_graph_prune.argtypes = [vp, i64, i32, i32, vp, vp]
         L.ann_graph_prune.restype = ctypes.c_int
         L.ann_graph_optimize_workspace_bytes.argtypes = [i64, i32, i32]
@@ -291,3 +293,15 @@ def ann_graph_optimize(knn: torch.Tensor, d_out: int, out_graph: torch.Tensor = 
     if stream is not None:
         workspace.record_stream(stream)
     return out_graph
+
+
+def ann_calibration_gather(h: Handle, ids: torch.Tensor, sink: torch.Tensor = None, stream=None) -> torch.Tensor:
+    """Reads the rows of `ids` (int32, any shape) and xors them into `sink` (one int32, zeroed here if not given)."""
+    if ids.dtype != torch.int32 or not ids.is_contiguous():
+        raise ValueError("ids must be a contiguous int32 tensor")
+    if sink is None:
+        sink = torch.zeros(1, dtype=torch.int32, device=ids.device)
+    if sink.dtype != torch.int32 or sink.numel() != 1:
+        raise ValueError("sink must hold one int32")
+    _check(lib().ann_calibration_gather(h.ptr, _dev_ptr(ids, "ids"), ids.numel(), _dev_ptr(sink, "sink"), _stream(stream)))
+    return sink

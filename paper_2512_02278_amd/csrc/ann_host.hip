@@ -451,6 +451,73 @@ __global__ void __launch_bounds__(256) ann_calibration_copy_kernel(uint4* __rest
 }
 }  // namespace ann
 
+namespace ann {
+// Piece p (16 bytes) is piece p % pieces of row p / pieces.  A workgroup takes 8 * 256 consecutive pieces at a
+// time (256 whole rows of 128 bytes) and every thread has its eight loads in flight before it uses one.
+__global__ void __launch_bounds__(256) ann_calibration_gather_kernel(const uint8_t* __restrict__ vectors, int64_t n,
+                                                                     int64_t row_stride, int pieces, int piece_shift,
+                                                                     const int32_t* __restrict__ ids, int64_t count,
+                                                                     uint32_t* sink) {
+    __shared__ uint32_t part[256];
+    const int64_t total = count * pieces;
+    uint32_t acc = 0;
+    // the ids of the next chunk are fetched while the rows of the current one are in flight
+    auto id_of = [&](int64_t p) -> int32_t {
+        if (p >= total) return -1;
+        return ids[piece_shift >= 0 ? p >> piece_shift : p / pieces];
+    };
+    const int64_t step = (int64_t)gridDim.x * 2048;
+    int64_t base = (int64_t)blockIdx.x * 2048;
+    int32_t id[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) id[u] = id_of(base + u * 256 + threadIdx.x);
+    for (; base < total; base += step) {
+        typedef uint32_t word4 __attribute__((ext_vector_type(4)));
+        word4 x[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int64_t p = base + u * 256 + threadIdx.x;
+            x[u] = word4{0u, 0u, 0u, 0u};
+            if (id[u] >= 0 && (int64_t)id[u] < n) {
+                const int64_t r = piece_shift >= 0 ? p >> piece_shift : p / pieces;
+                // no row is read twice: non-temporal loads keep them from displacing each other in L2
+                x[u] = __builtin_nontemporal_load(
+                    reinterpret_cast<const word4*>(vectors + (int64_t)id[u] * row_stride + (p - r * pieces) * 16));
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) id[u] = id_of(base + step + u * 256 + threadIdx.x);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc ^= x[u].x ^ x[u].y ^ x[u].z ^ x[u].w;
+    }
+    part[threadIdx.x] = acc;
+    __syncthreads();
+    for (int w = 128; w > 0; w >>= 1) {
+        if ((int)threadIdx.x < w) part[threadIdx.x] ^= part[threadIdx.x + w];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) atomicXor(sink, part[0]);
+}
+}  // namespace ann
+
+extern "C" int ann_calibration_gather(ann_index_t* h, const int32_t* ids, int64_t count, uint32_t* sink, void* stream) {
+    if (!h || h->magic != kMagic) return fail(ANN_EINVAL, "ann_calibration_gather: not a live handle");
+    if (count < 0) return fail(ANN_EINVAL, "ann_calibration_gather: count = %lld", (long long)count);
+    if (count == 0) return ANN_OK;
+    if (!ids || !sink) return fail(ANN_EINVAL, "ann_calibration_gather: null argument");
+    const int pieces = h->row_bytes / 16;
+    int shift = -1;
+    for (int b = 0; b < 12; ++b)
+        if ((1 << b) == pieces) shift = b;
+    const int64_t want = (count * pieces + 2047) / 2048;  // eight pieces per thread
+    const unsigned blocks = (unsigned)(want < 1 ? 1 : want > 2048 ? 2048 : want);  // 8 workgroups of 4 wavefronts per compute unit
+    hipLaunchKernelGGL(ann::ann_calibration_gather_kernel, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       static_cast<const uint8_t*>(h->d.vectors), h->d.n, h->d.row_stride_bytes, pieces, shift, ids, count,
+                       sink);
+    const hipError_t e = hipGetLastError();
+    return e == hipSuccess ? ANN_OK : fail(ANN_EHIP, "ann_calibration_gather: launch failed: %s", hipGetErrorString(e));
+}
+
 extern "C" int ann_calibration_copy(void* dst, const void* src, int64_t bytes, void* stream) {
     if (!dst || !src || bytes < 0 || bytes % 16 != 0 || !aligned16(dst) || !aligned16(src))
         return fail(ANN_EINVAL, "ann_calibration_copy: pointers must be non-null and 16-byte aligned, bytes a multiple of 16");

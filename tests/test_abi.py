@@ -134,6 +134,13 @@ def test_combine_entry_points_reject_bad_arguments():
     assert merge(k=0) == ann.ANN_EINVAL
     assert merge(ids=None) == ann.ANN_EINVAL
     assert merge(ok=None) == ann.ANN_EINVAL
+    rc, h2 = load(desc())
+    assert L.ann_calibration_gather(h2, FAKE, 0, FAKE, None) == ann.ANN_OK
+    assert L.ann_calibration_gather(h2, None, 8, FAKE, None) == ann.ANN_EINVAL
+    assert L.ann_calibration_gather(h2, FAKE, 8, None, None) == ann.ANN_EINVAL
+    assert L.ann_calibration_gather(h2, FAKE, -3, FAKE, None) == ann.ANN_EINVAL
+    assert L.ann_calibration_gather(None, FAKE, 8, FAKE, None) == ann.ANN_EINVAL
+    assert L.ann_free(h2) == ann.ANN_OK
     assert L.ann_calibration_copy(FAKE, FAKE, 0, None) == ann.ANN_OK
     assert L.ann_calibration_copy(FAKE, FAKE, 24, None) == ann.ANN_EINVAL      # not a multiple of 16
     assert L.ann_calibration_copy(None, FAKE, 32, None) == ann.ANN_EINVAL

@@ -459,6 +459,29 @@ def test_route_and_search_of_consecutive_batches_on_two_streams(oracle, torch_cu
     ann.ann_free(h)
 
 
+def test_calibration_gather_reads_exactly_the_rows(torch_cuda):
+    """The measurement aid xors every 32-bit word of the rows it is given; ids outside the table are skipped."""
+    from paper_2512_02278_amd import ann
+
+    torch = torch_cuda
+    rng = np.random.default_rng(5)
+    for dt, dim in ((np.uint8, 128), (np.float32, 96), (np.float16, 768), (np.uint8, 48)):
+        n = 3000
+        x = rng.integers(0, 256, (n, dim * np.dtype(dt).itemsize), dtype=np.uint8).view(dt)
+        if dt != np.uint8:
+            x = np.nan_to_num(x, nan=1.0, posinf=1.0, neginf=-1.0)
+        g = np.zeros((n, 4), np.int32)
+        h = ann.ann_index_load(torch.from_numpy(x).to("cuda:0"), torch.from_numpy(g).to("cuda:0"), n_entry=4)
+        ids = rng.integers(0, n, 5001).astype(np.int32)
+        ids[[7, 99]] = [-1, n]
+        sink = ann.ann_calibration_gather(h, torch.from_numpy(ids).to("cuda:0"))
+        torch.cuda.synchronize()
+        ann.ann_free(h)
+        ok = (ids >= 0) & (ids < n)
+        want = np.bitwise_xor.reduce(np.ascontiguousarray(x[ids[ok]]).view(np.uint32).ravel())
+        assert np.uint32(sink.cpu().numpy().view(np.uint32)[0]) == want
+
+
 # ----------------------------------------------------------------------------- the bench's workload at full size
 def test_hundred_million_partition_sampled_against_oracle(oracle, torch_cuda):
     """Config 4 at full size (100M x 128 uint8, 16384 clusters, degree 32) in the launch shape the
