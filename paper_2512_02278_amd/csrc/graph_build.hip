@@ -64,14 +64,14 @@ __device__ __forceinline__ int match_in(const uint4 t, uint32_t id) {
 template <int B>
 __device__ __forceinline__ void rank_table_insert(uint32_t* tid, uint8_t* trk, uint32_t id, int rank) {
     uint32_t b = bucket_of<B>(id);
-    for (;;) {  // ends: the row's ids fill at most a sixteenth of the slots
+    for (;;) {  // ends: the row's ids fill at most an eighth of the slots
         for (int s = 0; s < 4; ++s) {
             const uint32_t old = atomicCAS(&tid[4 * b + s], kEmptyId, id);
             if (old == kEmptyId) {
                 trk[4 * b + s] = (uint8_t)rank;
                 return;
             }
-            if (old == id) return;  // a repeated id keeps the rank that came first
+            if (old == id) return;  // a repeated id (not allowed in a row) keeps one of its ranks
         }
         b = (b + 1) & (B - 1);
     }
