@@ -26,6 +26,19 @@ def test_library_exports_every_declared_symbol():
         assert getattr(L, name) is not None
 
 
+def test_public_header_is_plain_c(tmp_path):
+    """include/ann.h is the boundary: it must compile as C99 and as C++ on its own, with no HIP or torch types."""
+    import subprocess
+
+    src = tmp_path / "use_header.c"
+    src.write_text('#include "ann.h"\nint main(void) { return ANN_OK; }\n')
+    inc = os.path.join(ROOT, "include")
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", "-I", inc, str(src)], check=True)
+    subprocess.run(["g++", "-std=c++17", "-Wall", "-Werror", "-fsyntax-only", "-x", "c++", "-I", inc, str(src)], check=True)
+    text = re.sub(r"/\*.*?\*/", "", open(os.path.join(inc, "ann.h")).read(), flags=re.S)
+    assert "hip" not in text.lower() and "torch" not in text.lower() and "#include <stdint.h>" in text
+
+
 def desc(**kw):
     d = ann.ann_index_desc_t()
     d.vectors, d.n, d.dim, d.dtype, d.row_stride_bytes = FAKE, 1000, 128, ann.ANN_U8, 128
