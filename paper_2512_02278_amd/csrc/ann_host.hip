@@ -455,17 +455,16 @@ namespace ann {
 // Piece p (16 bytes) is piece p % pieces of row p / pieces.  A workgroup takes 8 * 256 consecutive pieces at a
 // time (256 whole rows of 128 bytes) and every thread has its eight loads in flight before it uses one.
 __global__ void __launch_bounds__(256) ann_calibration_gather_kernel(const uint8_t* __restrict__ vectors, int64_t n,
-                                                                     int64_t row_stride, int pieces, int piece_shift,
+                                                                     int64_t row_stride, int pieces, uint64_t pieces_inv,
                                                                      const int32_t* __restrict__ ids, int64_t count,
                                                                      uint32_t* sink) {
     __shared__ uint32_t part[256];
     const int64_t total = count * pieces;
     uint32_t acc = 0;
     // the ids of the next chunk are fetched while the rows of the current one are in flight
-    auto id_of = [&](int64_t p) -> int32_t {
-        if (p >= total) return -1;
-        return ids[piece_shift >= 0 ? p >> piece_shift : p / pieces];
-    };
+    // p / pieces as the high half of p * ceil(2^64 / pieces): exact for p < 2^41, pieces <= 128
+    auto row_of = [&](int64_t p) -> int64_t { return pieces == 1 ? p : (int64_t)__umul64hi((uint64_t)p, pieces_inv); };
+    auto id_of = [&](int64_t p) -> int32_t { return p < total ? ids[row_of(p)] : -1; };
     const int64_t step = (int64_t)gridDim.x * 2048;
     int64_t base = (int64_t)blockIdx.x * 2048;
     int32_t id[8];
@@ -479,7 +478,7 @@ __global__ void __launch_bounds__(256) ann_calibration_gather_kernel(const uint8
             const int64_t p = base + u * 256 + threadIdx.x;
             x[u] = word4{0u, 0u, 0u, 0u};
             if (id[u] >= 0 && (int64_t)id[u] < n) {
-                const int64_t r = piece_shift >= 0 ? p >> piece_shift : p / pieces;
+                const int64_t r = row_of(p);
                 // no row is read twice: non-temporal loads keep them from displacing each other in L2
                 x[u] = __builtin_nontemporal_load(
                     reinterpret_cast<const word4*>(vectors + (int64_t)id[u] * row_stride + (p - r * pieces) * 16));
@@ -505,14 +504,13 @@ extern "C" int ann_calibration_gather(ann_index_t* h, const int32_t* ids, int64_
     if (count < 0) return fail(ANN_EINVAL, "ann_calibration_gather: count = %lld", (long long)count);
     if (count == 0) return ANN_OK;
     if (!ids || !sink) return fail(ANN_EINVAL, "ann_calibration_gather: null argument");
-    const int pieces = h->row_bytes / 16;
-    int shift = -1;
-    for (int b = 0; b < 12; ++b)
-        if ((1 << b) == pieces) shift = b;
+    const int pieces = h->row_bytes / 16;  // at most 128 (2048-byte rows)
+    if (count > (int64_t)1 << 33) return fail(ANN_EUNSUPPORTED, "ann_calibration_gather: count above 2^33");
+    const uint64_t pieces_inv = pieces == 1 ? 0 : (~0ull) / (uint64_t)pieces + 1;  // ceil(2^64 / pieces)
     const int64_t want = (count * pieces + 2047) / 2048;  // eight pieces per thread
     const unsigned blocks = (unsigned)(want < 1 ? 1 : want > 2048 ? 2048 : want);  // 8 workgroups of 4 wavefronts per compute unit
     hipLaunchKernelGGL(ann::ann_calibration_gather_kernel, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(stream),
-                       static_cast<const uint8_t*>(h->d.vectors), h->d.n, h->d.row_stride_bytes, pieces, shift, ids, count,
+                       static_cast<const uint8_t*>(h->d.vectors), h->d.n, h->d.row_stride_bytes, pieces, pieces_inv, ids, count,
                        sink);
     const hipError_t e = hipGetLastError();
     return e == hipSuccess ? ANN_OK : fail(ANN_EHIP, "ann_calibration_gather: launch failed: %s", hipGetErrorString(e));

@@ -465,7 +465,7 @@ def test_calibration_gather_reads_exactly_the_rows(torch_cuda):
 
     torch = torch_cuda
     rng = np.random.default_rng(5)
-    for dt, dim in ((np.uint8, 128), (np.float32, 96), (np.float16, 768), (np.uint8, 48)):
+    for dt, dim in ((np.uint8, 128), (np.float32, 96), (np.float16, 768), (np.uint8, 48), (np.uint8, 16)):
         n = 3000
         x = rng.integers(0, 256, (n, dim * np.dtype(dt).itemsize), dtype=np.uint8).view(dt)
         if dt != np.uint8:
