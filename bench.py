@@ -52,6 +52,7 @@ WORKLOADS = {
                          "cluster-restricted kNN graph, L2"),
     "text20m": dict(kind="unit", dtype="f16", metric="ip", n=20_000_000, centres=8192, dim=768, degree=64, nq=50_000,
                     k=100, width=8, max_iters=200, itopk_sweep=(256,), sweep=(1_000, 10_000, 50_000),
+                    optimize_from=128, opt_itopk_sweep=(100, 104, 112, 128, 160, 192, 256),
                     text="20M x 768 fp16 text-embedding-like index (unit-norm mixture, 8192 centres, rho 0.5), "
                          "degree-64 cluster-restricted kNN graph, inner product, fp32 accumulation"),
 }
