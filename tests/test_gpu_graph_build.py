@@ -141,3 +141,31 @@ def test_million_node_graph_sampled(oracle, torch_cuda):
     srt = torch.sort(out, dim=1).values
     assert int((srt[:, 1:] == srt[:, :-1]).sum()) == 0
     assert int((out == torch.arange(out.shape[0], device=out.device, dtype=torch.int32)[:, None]).sum()) == 0
+
+
+def test_search_on_the_graph_the_gpu_built(oracle, torch_cuda):
+    """The whole path at small size: kNN lists -> ann_graph_optimize -> ann_search on that graph, both against
+    the oracle (graph rows identical, then ids and int32 keys of the search identical)."""
+    torch = torch_cuda
+    from paper_2512_02278_amd import ann, inputs
+
+    part = inputs.sift_like(20_000, 20, seed=9, device=torch.device("cuda:0"))
+    knn = inputs.knn_graph_clustered(part, 48)
+    graph = ann.ann_graph_optimize(knn, 24)
+    torch.cuda.synchronize()
+    want_graph = oracle.graph_optimize(knn.cpu().numpy(), 24)
+    assert np.array_equal(graph.cpu().numpy(), want_graph)
+    q = inputs.sift_like_queries(part, 500)
+    h = ann.ann_index_load(part.vectors, graph, n_entry=32, entry_mode=ann.ANN_ENTRY_ROUTED, seed=5,
+                           centroids=part.centres, cluster_offsets=part.offsets, route_c=2)
+    cnt = torch.zeros((500, 4), dtype=torch.int32, device="cuda:0")
+    ids, dists = ann.ann_search(h, q, 10, 96, 4, 100, counters=cnt)
+    torch.cuda.synchronize()
+    ann.ann_free(h)
+    ix = oracle.Index(part.vectors.cpu().numpy(), want_graph, n_entry=32, entry_mode=1, seed=5,
+                      centroids=part.centres.cpu().numpy(), cluster_offsets=part.offsets.cpu().numpy(), route_c=2)
+    oi, od, oc = oracle.search(ix, q.cpu().numpy(), 10, 96, 4, 100)
+    assert np.array_equal(ids.cpu().numpy(), oi) and np.array_equal(dists.cpu().numpy(), od)
+    assert np.array_equal(cnt[:, 0].cpu().numpy(), oc["iters"])
+    truth = inputs.ground_truth(part, q, 10)
+    assert inputs.recall(ids, truth) > 0.95
