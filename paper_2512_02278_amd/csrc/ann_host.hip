@@ -426,7 +426,7 @@ extern "C" int ann_graph_prune(const int32_t* knn, int64_t n, int d_in, int d_ou
 
 extern "C" int64_t ann_graph_optimize_workspace_bytes(int64_t n, int d_in, int d_out) {
     if (const int rc = check_graph_shape("ann_graph_optimize_workspace_bytes", n, d_in, d_out)) return rc;
-    return ((n * d_out * 4 + 255) & ~(int64_t)255) + graph_reverse_merge_scratch_bytes(n, d_out);
+    return graph_optimize_scratch_bytes(n, d_out);
 }
 
 extern "C" int ann_graph_optimize(const int32_t* knn, int64_t n, int d_in, int d_out, int32_t* out_graph, void* workspace,
@@ -437,10 +437,7 @@ extern "C" int ann_graph_optimize(const int32_t* knn, int64_t n, int d_in, int d
     const int64_t need = ann_graph_optimize_workspace_bytes(n, d_in, d_out);
     if (workspace_bytes < need)
         return fail(ANN_EINVAL, "ann_graph_optimize: workspace of %lld bytes, %lld needed", (long long)workspace_bytes, (long long)need);
-    int32_t* pruned = static_cast<int32_t*>(workspace);
-    char* rest = static_cast<char*>(workspace) + ((n * d_out * 4 + 255) & ~(int64_t)255);
-    hipError_t e = launch_graph_prune(knn, n, d_in, d_out, pruned, static_cast<hipStream_t>(stream));
-    if (e == hipSuccess) e = launch_graph_reverse_merge(pruned, n, d_out, out_graph, rest, static_cast<hipStream_t>(stream));
+    const hipError_t e = launch_graph_optimize(knn, n, d_in, d_out, out_graph, workspace, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? ANN_OK : fail(ANN_EHIP, "ann_graph_optimize: launch failed: %s", hipGetErrorString(e));
 }
 

@@ -18,8 +18,9 @@
 // on one XCD so that its L2 serves the re-reads.  The ids of x's row go into a small LDS table
 // (id -> rank); the ids of every neighbour's row pass a Bloom filter of x's row, and those that
 // survive are looked up in the table and bump an LDS counter.
-// Step 3 is a counting sort by target (histogram, scan, scatter of (position, source) words) followed
-// by a selection per node, so that the result does not depend on the order in which the atomics land.
+// Step 3 is a counting sort by target (histogram - counted by the pruning kernel itself -, scan,
+// scatter of (position, source) words) followed by a selection per node, so that the result does not
+// depend on the order in which the atomics land.
 #include <hip/hip_runtime.h>
 
 #include "graph_build.h"
@@ -100,9 +101,14 @@ __device__ __forceinline__ int rank_table_find(const uint32_t* tid, uint32_t id,
 // Only about one id in ten of a neighbour's row is also in x's row (clustered 128-d data), so the
 // ids first pass a one-hash Bloom filter of x's row (2048 * R bits in LDS, one 4-byte read each);
 // the survivors are queued in LDS with the later of their two ranks and looked up 64 at a time.
-template <int R>
+//
+// COUNT: the kernel also counts the in-edges of the pruned graph (step 3's histogram) - one returning
+// atomic per pruned edge, whose result is the edge's slot in its target's list.  The atomics are
+// memory-side work that overlaps this kernel's instruction-bound lookups, instead of a pass of its own.
+template <int R, bool COUNT>
 __global__ void __launch_bounds__(64) graph_prune_kernel(const int32_t* __restrict__ knn, int64_t n, int d_in, int d_out,
-                                                         int32_t* __restrict__ pruned, int64_t runs_per_xcd) {
+                                                         int32_t* __restrict__ pruned, int64_t runs_per_xcd,
+                                                         uint32_t* indeg, uint32_t* __restrict__ slot) {
     constexpr int B = 128 * R, U = 8, kBloomBits = 11 + (R > 1), kQueue = 128;
     __shared__ __align__(16) uint32_t tid[4 * B];   // ids of x's row, by bucket
     __shared__ uint8_t trk[4 * B];                  // their ranks
@@ -214,7 +220,11 @@ __global__ void __launch_bounds__(64) graph_prune_kernel(const int32_t* __restri
         for (int r = 0; r < R; ++r)
             if (have[r] && pos[r] < d_out) orow[pos[r]] = mine[r];
         wave_lds_sync();
-        if (lane < d_out) pruned[x * d_out + lane] = orow[lane];
+        if (lane < d_out) {
+            const int32_t y = orow[lane];  // a present id or -1
+            pruned[x * d_out + lane] = y;
+            if (COUNT && y >= 0) slot[x * d_out + lane] = atomicAdd(&indeg[y], 1u);
+        }
         wave_lds_sync();
     }
 }
@@ -224,7 +234,7 @@ __global__ void __launch_bounds__(256) fill_zero_u32_kernel(uint32_t* p, int64_t
     for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) p[i] = 0u;
 }
 
-// Chunk of 256 nodes a workgroup of the two edge kernels works on: like the node runs above, the chunks
+// Chunk of 256 nodes a workgroup of the edge kernel works on: like the node runs above, the chunks
 // are dealt so that an XCD walks a contiguous eighth of the ids; the edges of neighbouring nodes point
 // into the same few clusters, and their 8-byte words then meet in one L2 before they are written back.
 __device__ __forceinline__ int64_t chunk_of(int64_t b, int64_t chunks_per_xcd) { return (b & 7) * chunks_per_xcd + (b >> 3); }
@@ -232,19 +242,6 @@ __device__ __forceinline__ int64_t chunk_of(int64_t b, int64_t chunks_per_xcd) {
 // Chunk c covers the 256 nodes from 256 * c on: element t of their rows is
 // node 256 * c + t / d, position t % d, with t / d == (t * d_inv) >> 22 for t < 256 * d, d <= 64
 // (d_inv = ceil(2^22 / d)).
-//
-// indeg[y] <- number of edges into y; slot[e] <- how many of them were counted before edge e
-__global__ void __launch_bounds__(256) in_degree_kernel(const int32_t* __restrict__ g, int64_t n, int d, uint32_t d_inv,
-                                                        uint32_t* indeg, uint32_t* __restrict__ slot, int64_t chunks_per_xcd) {
-    const int64_t xb = chunk_of(blockIdx.x, chunks_per_xcd) * 256;
-    const int rows = n - xb < 256 ? (n > xb ? (int)(n - xb) : 0) : 256;
-    for (int t = threadIdx.x; t < rows * d; t += 256) {
-        const int64_t x = xb + (int)(((uint32_t)t * d_inv) >> 22);
-        const int32_t y = g[xb * d + t];
-        if (is_present(y, n, x)) slot[xb * d + t] = atomicAdd(&indeg[y], 1u);
-    }
-}
-
 // Exclusive scan of indeg[0..n) into off[0..n] (64-bit), in three launches: per-chunk sums, a scan of
 // those by one workgroup, then every chunk scans itself on top of its prefix.
 __global__ void __launch_bounds__(256) chunk_sums_kernel(const uint32_t* __restrict__ deg, int64_t n, int64_t* sums) {
@@ -396,36 +393,56 @@ int64_t runs_per_xcd_of(int64_t n) {
 
 }  // namespace
 
-hipError_t launch_graph_prune(const int32_t* knn, int64_t n, int d_in, int d_out, int32_t* pruned, hipStream_t stream) {
+namespace {
+
+hipError_t launch_prune(const int32_t* knn, int64_t n, int d_in, int d_out, int32_t* pruned, uint32_t* indeg,
+                        uint32_t* slot, hipStream_t stream) {
     const int64_t rpx = runs_per_xcd_of(n);
-    if (d_in <= 64)
-        hipLaunchKernelGGL(graph_prune_kernel<1>, dim3((unsigned)(8 * rpx)), dim3(64), 0, stream, knn, n, d_in, d_out, pruned, rpx);
+    const dim3 grid((unsigned)(8 * rpx)), block(64);
+    if (d_in <= 64 && indeg)
+        hipLaunchKernelGGL((graph_prune_kernel<1, true>), grid, block, 0, stream, knn, n, d_in, d_out, pruned, rpx, indeg, slot);
+    else if (d_in <= 64)
+        hipLaunchKernelGGL((graph_prune_kernel<1, false>), grid, block, 0, stream, knn, n, d_in, d_out, pruned, rpx, indeg, slot);
+    else if (indeg)
+        hipLaunchKernelGGL((graph_prune_kernel<2, true>), grid, block, 0, stream, knn, n, d_in, d_out, pruned, rpx, indeg, slot);
     else
-        hipLaunchKernelGGL(graph_prune_kernel<2>, dim3((unsigned)(8 * rpx)), dim3(64), 0, stream, knn, n, d_in, d_out, pruned, rpx);
+        hipLaunchKernelGGL((graph_prune_kernel<2, false>), grid, block, 0, stream, knn, n, d_in, d_out, pruned, rpx, indeg, slot);
     return hipGetLastError();
 }
 
-// scratch layout: indeg (n u32) | off (n + 1 i64) | chunk sums (i64) | pairs (n * d u64)
-int64_t graph_reverse_merge_scratch_bytes(int64_t n, int d) {
-    const int64_t chunks = (n + kScanChunk - 1) / kScanChunk;
-    return align256(n * 4) + align256((n + 1) * 8) + align256(chunks * 8) + align256(n * d * 8);
+}  // namespace
+
+hipError_t launch_graph_prune(const int32_t* knn, int64_t n, int d_in, int d_out, int32_t* pruned, hipStream_t stream) {
+    return launch_prune(knn, n, d_in, d_out, pruned, nullptr, nullptr, stream);
 }
 
-hipError_t launch_graph_reverse_merge(const int32_t* pruned, int64_t n, int d, int32_t* out, void* scratch,
-                                      hipStream_t stream) {
+// scratch layout: pruned (n * d i32) | indeg (n u32) | off (n + 1 i64) | chunk sums (i64) | pairs (n * d u64)
+int64_t graph_optimize_scratch_bytes(int64_t n, int d) {
+    const int64_t chunks = (n + kScanChunk - 1) / kScanChunk;
+    return align256(n * d * 4) + align256(n * 4) + align256((n + 1) * 8) + align256(chunks * 8) + align256(n * d * 8);
+}
+
+hipError_t launch_graph_optimize(const int32_t* knn, int64_t n, int d_in, int d, int32_t* out, void* scratch,
+                                 hipStream_t stream) {
     const int64_t chunks = (n + kScanChunk - 1) / kScanChunk;
     char* base = static_cast<char*>(scratch);
+    int32_t* pruned = reinterpret_cast<int32_t*>(base);
+    base += align256(n * d * 4);
     uint32_t* indeg = reinterpret_cast<uint32_t*>(base);
-    int64_t* off = reinterpret_cast<int64_t*>(base + align256(n * 4));
-    int64_t* sums = reinterpret_cast<int64_t*>(base + align256(n * 4) + align256((n + 1) * 8));
-    uint64_t* pairs = reinterpret_cast<uint64_t*>(base + align256(n * 4) + align256((n + 1) * 8) + align256(chunks * 8));
+    base += align256(n * 4);
+    int64_t* off = reinterpret_cast<int64_t*>(base);
+    base += align256((n + 1) * 8);
+    int64_t* sums = reinterpret_cast<int64_t*>(base);
+    base += align256(chunks * 8);
+    uint64_t* pairs = reinterpret_cast<uint64_t*>(base);
     // until the last kernel writes it, `out` holds the slot of every edge within its target's list
     uint32_t* slot = reinterpret_cast<uint32_t*>(out);
     const uint32_t d_inv = (uint32_t)(((1u << 22) + d - 1) / d);
     const int64_t chunks_per_xcd = ((n + 255) / 256 + 7) / 8;
     const unsigned node_blocks = (unsigned)(8 * chunks_per_xcd);
     hipLaunchKernelGGL(fill_zero_u32_kernel, dim3(blocks_for(n)), dim3(256), 0, stream, indeg, n);
-    hipLaunchKernelGGL(in_degree_kernel, dim3(node_blocks), dim3(256), 0, stream, pruned, n, d, d_inv, indeg, slot, chunks_per_xcd);
+    const hipError_t e = launch_prune(knn, n, d_in, d, pruned, indeg, slot, stream);
+    if (e != hipSuccess) return e;
     hipLaunchKernelGGL(chunk_sums_kernel, dim3((unsigned)chunks), dim3(256), 0, stream, indeg, n, sums);
     hipLaunchKernelGGL(scan_sums_kernel, dim3(1), dim3(1024), 0, stream, sums, chunks);
     hipLaunchKernelGGL(offsets_kernel, dim3((unsigned)chunks), dim3(256), 0, stream, indeg, n, sums, off);
