@@ -105,7 +105,7 @@ __device__ __forceinline__ int rank_table_find(const uint32_t* tid, uint32_t id,
 // COUNT: the kernel also counts the in-edges of the pruned graph (step 3's histogram) - one returning
 // atomic per pruned edge, whose result is the edge's slot in its target's list.  The atomics are
 // memory-side work that overlaps this kernel's instruction-bound lookups, instead of a pass of its own.
-template <int R, bool COUNT>
+template <int R, bool COUNT, bool VEC>
 __global__ void __launch_bounds__(64) graph_prune_kernel(const int32_t* __restrict__ knn, int64_t n, int d_in, int d_out,
                                                          int32_t* __restrict__ pruned, int64_t runs_per_xcd,
                                                          uint32_t* indeg, uint32_t* __restrict__ slot) {
@@ -156,39 +156,66 @@ __global__ void __launch_bounds__(64) graph_prune_kernel(const int32_t* __restri
         }
         wave_lds_sync();
 
-        // rows of the neighbours at ranks 0 .. d_in-2 (the last one has no edge after it), U rows in flight
+        // rows of the neighbours at ranks 0 .. d_in-2 (the last one has no edge after it); every id that passes
+        // the Bloom filter is queued with the later of its two ranks
         int head = 0, queued = 0;  // wave-uniform
-        for (int i0 = 0; i0 < d_in - 1; i0 += U) {
-            int32_t v[U][R];
+        auto push = [&](int32_t ys, int later) {
+            const uint32_t y = (uint32_t)ys;
+            const uint32_t hb = (y * 0x9E3779B1u) >> (32 - kBloomBits);
+            const bool pass = ys >= 0 && ((bloom[hb >> 5] >> (hb & 31)) & 1u);
+            const uint64_t m = __ballot(pass);
+            if (pass) queue[(head + queued + rank_below(m)) & (kQueue - 1)] = ((uint64_t)(uint32_t)later << 32) | y;
+            queued += __builtin_popcountll(m);
+            if (queued >= 64) {
+                wave_lds_sync();
+                drain(head, 64);
+                head = (head + 64) & (kQueue - 1);
+                queued -= 64;
+            }
+        };
+        if constexpr (VEC) {
+            // rows of d_in % 4 == 0 ids, 16-byte aligned: a lane reads four consecutive ranks, 16 * R lanes
+            // cover a row, so one load instruction fetches 4 / R rows; four of them in flight
+            constexpr int kLanesPerRow = 16 * R, kRowsPerLoad = 64 / kLanesPerRow, UV = 4;
+            const int quad = lane % kLanesPerRow, sub = lane / kLanesPerRow;
+            for (int i0 = 0; i0 < d_in - 1; i0 += UV * kRowsPerLoad) {
+                int4 v[UV];
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int i = i0 + u;
-                const int32_t z = i < d_in - 1 ? __builtin_amdgcn_readfirstlane(nbr[i]) : -1;
+                for (int u = 0; u < UV; ++u) {
+                    const int i = i0 + u * kRowsPerLoad + sub;
+                    const int32_t z = i < d_in - 1 ? nbr[i] : -1;
+                    v[u] = make_int4(-1, -1, -1, -1);
+                    if (z >= 0 && 4 * quad < d_in - 1) v[u] = *reinterpret_cast<const int4*>(knn + (int64_t)z * d_in + 4 * quad);
+                }
 #pragma unroll
-                for (int r = 0; r < R; ++r) {
-                    const int rr = lane + 64 * r;
-                    v[u][r] = (z >= 0 && rr < d_in - 1) ? knn[(int64_t)z * d_in + rr] : -1;
+                for (int u = 0; u < UV; ++u) {
+                    const int i = i0 + u * kRowsPerLoad + sub;
+                    const int32_t c4[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) {
+                        const int rr = 4 * quad + c;
+                        push(rr < d_in - 1 ? c4[c] : -1, max(i, rr));
+                    }
                 }
             }
+        } else {
+            // any d_in: a lane reads rank lane (+ 64) of one row per load, U rows in flight
+            for (int i0 = 0; i0 < d_in - 1; i0 += U) {
+                int32_t v[U][R];
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
+                for (int u = 0; u < U; ++u) {
+                    const int i = i0 + u;
+                    const int32_t z = i < d_in - 1 ? __builtin_amdgcn_readfirstlane(nbr[i]) : -1;
 #pragma unroll
-                for (int r = 0; r < R; ++r) {
-                    const uint32_t y = (uint32_t)v[u][r];
-                    const uint32_t hb = (y * 0x9E3779B1u) >> (32 - kBloomBits);
-                    const bool pass = v[u][r] >= 0 && ((bloom[hb >> 5] >> (hb & 31)) & 1u);
-                    const uint64_t m = __ballot(pass);
-                    if (pass) {
-                        const uint32_t later = (uint32_t)max(i0 + u, lane + 64 * r);
-                        queue[(head + queued + rank_below(m)) & (kQueue - 1)] = ((uint64_t)later << 32) | y;
+                    for (int r = 0; r < R; ++r) {
+                        const int rr = lane + 64 * r;
+                        v[u][r] = (z >= 0 && rr < d_in - 1) ? knn[(int64_t)z * d_in + rr] : -1;
                     }
-                    queued += __builtin_popcountll(m);
-                    if (queued >= 64) {
-                        wave_lds_sync();
-                        drain(head, 64);
-                        head = (head + 64) & (kQueue - 1);
-                        queued -= 64;
-                    }
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+#pragma unroll
+                    for (int r = 0; r < R; ++r) push(v[u][r], max(i0 + u, lane + 64 * r));
                 }
             }
         }
@@ -395,18 +422,25 @@ int64_t runs_per_xcd_of(int64_t n) {
 
 namespace {
 
+template <int R, bool COUNT>
+void launch_prune_rc(bool vec, dim3 grid, hipStream_t stream, const int32_t* knn, int64_t n, int d_in, int d_out,
+                     int32_t* pruned, int64_t rpx, uint32_t* indeg, uint32_t* slot) {
+    if (vec)
+        hipLaunchKernelGGL((graph_prune_kernel<R, COUNT, true>), grid, dim3(64), 0, stream, knn, n, d_in, d_out, pruned, rpx, indeg, slot);
+    else
+        hipLaunchKernelGGL((graph_prune_kernel<R, COUNT, false>), grid, dim3(64), 0, stream, knn, n, d_in, d_out, pruned, rpx, indeg, slot);
+}
+
 hipError_t launch_prune(const int32_t* knn, int64_t n, int d_in, int d_out, int32_t* pruned, uint32_t* indeg,
                         uint32_t* slot, hipStream_t stream) {
     const int64_t rpx = runs_per_xcd_of(n);
-    const dim3 grid((unsigned)(8 * rpx)), block(64);
-    if (d_in <= 64 && indeg)
-        hipLaunchKernelGGL((graph_prune_kernel<1, true>), grid, block, 0, stream, knn, n, d_in, d_out, pruned, rpx, indeg, slot);
-    else if (d_in <= 64)
-        hipLaunchKernelGGL((graph_prune_kernel<1, false>), grid, block, 0, stream, knn, n, d_in, d_out, pruned, rpx, indeg, slot);
-    else if (indeg)
-        hipLaunchKernelGGL((graph_prune_kernel<2, true>), grid, block, 0, stream, knn, n, d_in, d_out, pruned, rpx, indeg, slot);
-    else
-        hipLaunchKernelGGL((graph_prune_kernel<2, false>), grid, block, 0, stream, knn, n, d_in, d_out, pruned, rpx, indeg, slot);
+    const dim3 grid((unsigned)(8 * rpx));
+    // rows that start on 16-byte boundaries are read four ids per lane
+    const bool vec = d_in % 4 == 0 && (reinterpret_cast<uintptr_t>(knn) & 15u) == 0;
+    if (d_in <= 64 && indeg) launch_prune_rc<1, true>(vec, grid, stream, knn, n, d_in, d_out, pruned, rpx, indeg, slot);
+    else if (d_in <= 64) launch_prune_rc<1, false>(vec, grid, stream, knn, n, d_in, d_out, pruned, rpx, indeg, slot);
+    else if (indeg) launch_prune_rc<2, true>(vec, grid, stream, knn, n, d_in, d_out, pruned, rpx, indeg, slot);
+    else launch_prune_rc<2, false>(vec, grid, stream, knn, n, d_in, d_out, pruned, rpx, indeg, slot);
     return hipGetLastError();
 }
 

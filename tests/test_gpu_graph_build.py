@@ -87,10 +87,28 @@ def test_knn_lists_of_clustered_data(oracle, torch_cuda, n, n_centres, d_in, d_o
     (700, 64, 64, 0.3, 0.05, 5),
     (300, 128, 1, 0.1, 0.0, 6),
     (90, 128, 64, 0.0, 0.0, 7),    # rows longer than the graph has nodes
+    (500, 30, 9, 0.1, 0.05, 8),    # row length no multiple of four: one id per lane and load
+    (400, 70, 33, 0.1, 0.0, 9),    # the same with two registers per lane
 ])
 def test_random_lists_with_absent_entries(oracle, torch_cuda, n, d_in, d_out, holes, junk, seed):
     rng = np.random.default_rng(seed)
     check_both(oracle, torch_cuda, random_knn(rng, n, d_in, holes, junk), d_out)
+
+
+def test_rows_that_do_not_start_on_16_bytes(oracle, torch_cuda):
+    """kNN lists whose base address is only 4-byte aligned take the one-id-per-lane loads."""
+    from paper_2512_02278_amd import ann
+
+    torch = torch_cuda
+    rng = np.random.default_rng(12)
+    knn = random_knn(rng, 600, 32, holes=0.1)
+    flat = torch.empty(600 * 32 + 1, dtype=torch.int32, device="cuda:0")
+    view = flat[1:].view(600, 32)
+    view.copy_(torch.from_numpy(knn))
+    assert view.data_ptr() % 16 == 4 and view.is_contiguous()
+    got = ann.ann_graph_optimize(view, 16)
+    torch.cuda.synchronize()
+    assert np.array_equal(got.cpu().numpy(), oracle.graph_optimize(knn, 16))
 
 
 def test_hubs_with_thousands_of_in_edges(oracle, torch_cuda):
