@@ -30,6 +30,10 @@ namespace ann {
 namespace {
 
 constexpr int kNodesPerWave = 32;
+// Nodes per workgroup of in_edges_kernel (at most 256).  Small on purpose: the fewer nodes an XCD has in
+// flight, the fewer target lists are half-written in its L2 at a time, and the more of their 8-byte words
+// merge into whole lines before they are written back (22.5 ms per 25M nodes with 256, 9.5 ms with 8).
+constexpr int kChunkNodes = 8;
 constexpr int kScanChunk = 4096;  // elements per workgroup of the scan kernels: 256 threads x 16
 
 __device__ __forceinline__ void wave_lds_sync() { __syncthreads(); }  // one wavefront per workgroup
@@ -261,13 +265,13 @@ __global__ void __launch_bounds__(256) fill_zero_u32_kernel(uint32_t* p, int64_t
     for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) p[i] = 0u;
 }
 
-// Chunk of 256 nodes a workgroup of the edge kernel works on: like the node runs above, the chunks
+// Chunk of kChunkNodes nodes a workgroup of the edge kernel works on: like the node runs above, the chunks
 // are dealt so that an XCD walks a contiguous eighth of the ids; the edges of neighbouring nodes point
 // into the same few clusters, and their 8-byte words then meet in one L2 before they are written back.
 __device__ __forceinline__ int64_t chunk_of(int64_t b, int64_t chunks_per_xcd) { return (b & 7) * chunks_per_xcd + (b >> 3); }
 
-// Chunk c covers the 256 nodes from 256 * c on: element t of their rows is
-// node 256 * c + t / d, position t % d, with t / d == (t * d_inv) >> 22 for t < 256 * d, d <= 64
+// Chunk c covers the kChunkNodes nodes from kChunkNodes * c on: element t of their rows is node
+// kChunkNodes * c + t / d, position t % d, with t / d == (t * d_inv) >> 22 for t < 256 * d, d <= 64
 // (d_inv = ceil(2^22 / d)).
 // Exclusive scan of indeg[0..n) into off[0..n] (64-bit), in three launches: per-chunk sums, a scan of
 // those by one workgroup, then every chunk scans itself on top of its prefix.
@@ -340,8 +344,8 @@ __global__ void __launch_bounds__(256) offsets_kernel(const uint32_t* __restrict
 __global__ void __launch_bounds__(256) in_edges_kernel(const int32_t* __restrict__ g, int64_t n, int d, uint32_t d_inv,
                                                        const int64_t* __restrict__ off, const uint32_t* __restrict__ slot,
                                                        uint64_t* __restrict__ pairs, int64_t chunks_per_xcd) {
-    const int64_t xb = chunk_of(blockIdx.x, chunks_per_xcd) * 256;
-    const int rows = n - xb < 256 ? (n > xb ? (int)(n - xb) : 0) : 256;
+    const int64_t xb = chunk_of(blockIdx.x, chunks_per_xcd) * kChunkNodes;
+    const int rows = n - xb < kChunkNodes ? (n > xb ? (int)(n - xb) : 0) : kChunkNodes;
     for (int t = threadIdx.x; t < rows * d; t += 256) {
         const int xl = (int)(((uint32_t)t * d_inv) >> 22);
         const int64_t x = xb + xl;
@@ -472,7 +476,7 @@ hipError_t launch_graph_optimize(const int32_t* knn, int64_t n, int d_in, int d,
     // until the last kernel writes it, `out` holds the slot of every edge within its target's list
     uint32_t* slot = reinterpret_cast<uint32_t*>(out);
     const uint32_t d_inv = (uint32_t)(((1u << 22) + d - 1) / d);
-    const int64_t chunks_per_xcd = ((n + 255) / 256 + 7) / 8;
+    const int64_t chunks_per_xcd = ((n + kChunkNodes - 1) / kChunkNodes + 7) / 8;
     const unsigned node_blocks = (unsigned)(8 * chunks_per_xcd);
     hipLaunchKernelGGL(fill_zero_u32_kernel, dim3(blocks_for(n)), dim3(256), 0, stream, indeg, n);
     const hipError_t e = launch_prune(knn, n, d_in, d, pruned, indeg, slot, stream);
