@@ -372,6 +372,10 @@ __global__ void __launch_bounds__(64) graph_merge_kernel(const int32_t* __restri
         for (int64_t c0 = lo; c0 < hi; c0 += 64) {
             uint64_t v[1] = {c0 + lane < hi ? pairs[c0 + lane] : kInfKey};
             bitonic_sort<1>(v, lane);
+            if (c0 == lo) {  // the first chunk (the only one for most nodes) is the best so far as it is
+                best[0] = v[0];
+                continue;
+            }
             // element e of the best so far against element 63 - e of the sorted chunk keeps the 64
             // smallest of both, as one bitonic run
             const uint64_t o = xor_lane64<63>(v[0], lane);
