@@ -239,6 +239,9 @@ __global__ void __launch_bounds__(64) graph_prune_kernel(const int32_t* __restri
         int pos[R];
 #pragma unroll
         for (int r = 0; r < R; ++r) pos[r] = 0;
+        // fully unrolled, the 32 reads of two registers per lane would all be in flight and take 128 VGPRs
+        constexpr int kRankUnroll = R == 1 ? 16 : 4;
+#pragma unroll kRankUnroll
         for (int t = 0; t < 16 * R; ++t) {
             const uint4 k4 = reinterpret_cast<const uint4*>(key)[t];
 #pragma unroll
