@@ -182,7 +182,7 @@ struct BeamSearch {
 
     // Candidate ids held one per lane: keep the unseen ones, packed into cid[0..m).
     __device__ __forceinline__ void filter_into(int32_t id, bool valid, int& m) {
-        const int how = (valid && id >= 0 && (int64_t)id < p.n) ? visited_insert((uint32_t)id) : 0;
+        const int how = (valid && (uint32_t)id < (uint32_t)p.n) ? visited_insert((uint32_t)id) : 0;  // n < 2^31: a negative id fails too
         const uint64_t b = __ballot(how != 0);
         if (how != 0) cid[m + rank_below(b)] = (uint32_t)id;
         m += __builtin_popcountll(b);
