@@ -243,6 +243,12 @@ struct BeamSearch {
     // KMAX >= the number of real keys in the batch (a power of two, at most 64*R).
     template <int R, int KMAX>
     __device__ __forceinline__ void merge_batch(int base, int m) {
+        // The networks below test lane bits (dozens of per-lane conditions).  They do not change from
+        // round to round, so the compiler would compute them once, keep them as 64-bit scalar masks across
+        // the whole search loop and spill the loop's own scalars to make room; an opaque copy of the lane
+        // number makes it compute them here, on this rarely taken path.
+        int lane = this->lane;
+        asm volatile("" : "+v"(lane));
         uint64_t c[R];
 #pragma unroll
         for (int r = 0; r < R; ++r) {
