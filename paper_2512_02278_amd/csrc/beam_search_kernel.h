@@ -37,7 +37,7 @@
 #define ANN_INSERT_MAX 8
 #endif
 #ifndef ANN_MIN_WAVES
-#define ANN_MIN_WAVES 6
+#define ANN_MIN_WAVES 7
 #endif
 
 namespace ann {
@@ -453,8 +453,8 @@ struct BeamSearch {
 
 // Workgroup b runs on XCD b % 8 (round-robin dispatch), so consecutive queries are
 // kept on one XCD and its L2: query = (b % 8) * q_per_xcd + b / 8.
-// The small uint8 variants are asked to fit 7 wavefronts per SIMD (8 would push scalar registers into spills): with about
-// 5 KB of LDS per query that gives 28 queries in flight per CU.
+// The small uint8 variants are asked to fit 7 wavefronts per SIMD (72 vector registers; 8 would need spills):
+// with about 5.5 KB of LDS per query that is also what a compute unit's LDS holds, 28 queries in flight.
 template <class Row, int LPL, int CPL>
 __global__ void __launch_bounds__(64, (ANN_MIN_WAVES > 1 && Row::kDtype == kU8 && LPL <= 4 && CPL <= 2) ? ANN_MIN_WAVES : 1)
     beam_search_kernel(const SearchParams p) {
