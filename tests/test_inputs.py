@@ -68,3 +68,15 @@ def test_recall_counts_matches_and_ignores_padding():
     truth = torch.tensor([[3, 2, 7, 8], [9, 1, 2, 3]], dtype=torch.int32)
     # query 0 finds two of four; query 1 lists one true neighbour four times: it counts once
     assert abs(inputs.recall(found, truth) - (2 + 1) / 8) < 1e-9
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The build covers one GPU's partition: bench.py --gpus N (N > 1) must say so and exit non-zero."""
+    import os
+    import subprocess
+    import sys
+
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0 and "one GPU" in r.stderr and not r.stdout.strip()
