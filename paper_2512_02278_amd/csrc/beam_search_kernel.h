@@ -389,7 +389,7 @@ struct BeamSearch {
             bool un[LPL];
 #pragma unroll
             for (int r = 0; r < LPL; ++r) {
-                un[r] = (L[r] & 1ull) == 0;
+                un[r] = ((uint32_t)L[r] & 1u) == 0;
                 const uint64_t b = __ballot(un[r]);
                 before += rank_below(b);
                 total += __builtin_popcountll(b);
@@ -398,13 +398,10 @@ struct BeamSearch {
             const int np = total < p.width ? total : p.width;
 #pragma unroll
             for (int r = 0; r < LPL; ++r) {
-                if (un[r]) {
-                    if (before < np) {
-                        parents[before] = (uint32_t)L[r] >> 1;
-                        L[r] |= 1ull;
-                    }
-                    ++before;
-                }
+                const bool take = un[r] && before < np;
+                if (take) parents[before] = (uint32_t)L[r] >> 1;
+                L[r] |= (uint64_t)(take ? 1u : 0u);
+                before += un[r] ? 1 : 0;
             }
             n_parents += np;
             if (n_table + np * p.degree > limit) reset_table();
