@@ -281,7 +281,6 @@ struct BeamSearch {
         uint64_t* lcopy = ckey;
         const uint64_t mine = lane < s ? ckey[lane] : kInfKey;
         lds_sync();  // the new keys are in registers; their words may now be overwritten
-        for (int i = p.itopk + lane; i < 64 * LPL; i += 64) lcopy[i] = kInfKey;
         int cnt[LPL];
 #pragma unroll
         for (int r = 0; r < LPL; ++r) cnt[r] = 0;
@@ -300,12 +299,16 @@ struct BeamSearch {
             rank += c < mine ? 1 : 0;
             pos = lane == j ? below : pos;
         }
+        // Every key goes to its place without a test: a place may lie up to s <= kInsertMax entries beyond
+        // the copy (entries pushed off the end), which is still inside this round's scratch or, for the
+        // (4, 2) list variant, in the first words of `parents`, dead until the next round rewrites them.
+        // Whatever landed at or beyond itopk is then overwritten with the empty key.
+        static_assert(kInsertMax <= 8, "trash slots beyond the list copy");
 #pragma unroll
-        for (int r = 0; r < LPL; ++r) {
-            const int idx = lane * LPL + r + cnt[r];
-            if (idx < p.itopk) lcopy[idx] = L[r];
-        }
-        if (lane < s && pos + rank < p.itopk) lcopy[pos + rank] = mine;
+        for (int r = 0; r < LPL; ++r) lcopy[lane * LPL + r + cnt[r]] = L[r];
+        if (lane < s) lcopy[pos + rank] = mine;
+        lds_sync();
+        for (int i = p.itopk + lane; i < 64 * LPL; i += 64) lcopy[i] = kInfKey;
         lds_sync();
 #pragma unroll
         for (int r = 0; r < LPL; ++r) L[r] = lcopy[lane * LPL + r];
