@@ -166,6 +166,7 @@ def queries_near(rng, x, nq, dt):
     (128, 4, 32, 10, 32),    # the 1M / 100M configs' shape
     (100, 3, 40, 16, 100),   # batch 120, 100 entries
     (192, 4, 32, 10, 32),
+    (256, 4, 32, 10, 32),    # a full list of 4 registers per lane with a 2-register batch
     (256, 4, 64, 10, 32),    # the Deep-like config's shape
     (256, 8, 64, 100, 32),   # the text-like config's shape: 512 neighbours per round
     (512, 2, 48, 50, 500),
