@@ -117,6 +117,7 @@ struct BeamSearch {
     int n_windows;
     uint32_t w0_lo, w0_size;  // first window: ids [w0_lo, w0_lo + w0_size) are bits 0..
     int n_table;  // ids in the visited hash
+    uint64_t worst;  // list entry number itopk-1 (the empty key while the list is not full), kept up to date by merge_all
     int n_dist, n_parents, n_resets;
 
     // LDS layout, in 32-bit words.  Everything but the hash sits at a compile-time offset, so the
@@ -209,7 +210,7 @@ struct BeamSearch {
 #ifdef ANN_NO_WORST_FILTER
         const uint64_t worst = kInfKey;
 #else
-        const uint64_t worst = list_worst();
+        const uint64_t worst = this->worst;
 #endif
         int kept = 0;
         for (int j0 = 0; j0 < m; j0 += RPS * U) {
@@ -312,6 +313,7 @@ struct BeamSearch {
         lds_sync();
 #pragma unroll
         for (int r = 0; r < LPL; ++r) L[r] = lcopy[lane * LPL + r];
+        worst = lcopy[p.itopk - 1];  // one broadcast read of the sorted copy
         lds_sync();
     }
 
@@ -329,12 +331,14 @@ struct BeamSearch {
         } else if (m - base > 0) {
             merge_batch<1, 16>(base, m);
         }
+        if (m > 0) worst = list_worst();
     }
 
     __device__ __forceinline__ void run(int64_t qi) {
         row.load_query(p.queries + qi * (int64_t)p.row_bytes, p.row_bytes, lane);
 #pragma unroll
         for (int r = 0; r < LPL; ++r) L[r] = kInfKey;
+        worst = kInfKey;
         clear_table();
         for (int i = lane; i < (p.window_bits >> 5); i += 64) bitmap[i] = 0u;
         if (p.entry_mode == 1 && p.window_bits > 0) {
