@@ -185,7 +185,7 @@ struct BeamSearch {
     __device__ __forceinline__ void filter_into(int32_t id, bool valid, int& m) {
         const int how = (valid && (uint32_t)id < (uint32_t)p.n) ? visited_insert((uint32_t)id) : 0;  // n < 2^31: a negative id fails too
         const uint64_t b = __ballot(how != 0);
-        if (how != 0) cid[m + rank_below(b)] = (uint32_t)id;
+        if (how != 0) cid[rank_below(b, m)] = (uint32_t)id;
         m += __builtin_popcountll(b);
         n_table += __builtin_popcountll(__ballot(how == 2));
     }
@@ -232,7 +232,7 @@ struct BeamSearch {
                 const uint64_t packed = ((uint64_t)okey << 32) | ((uint64_t)id[u] << 1);
                 const bool keep = j < m && row.lg == 0 && packed < worst;
                 const uint64_t b = __ballot(keep);
-                if (keep) ckey[kept + rank_below(b)] = packed;
+                if (keep) ckey[rank_below(b, kept)] = packed;
                 kept += __builtin_popcountll(b);
             }
         }
@@ -398,7 +398,7 @@ struct BeamSearch {
             for (int r = 0; r < LPL; ++r) {
                 un[r] = ((uint32_t)L[r] & 1u) == 0;
                 const uint64_t b = __ballot(un[r]);
-                before += rank_below(b);
+                before = rank_below(b, before);
                 total += __builtin_popcountll(b);
             }
             if (total == 0) break;

@@ -17,9 +17,9 @@ __device__ __forceinline__ int lane_id() {
     return (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
 }
 
-// Number of set bits of `mask` below the calling lane.
-__device__ __forceinline__ int rank_below(uint64_t mask) {
-    return (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+// base + number of set bits of `mask` below the calling lane (the count instructions add to an operand).
+__device__ __forceinline__ int rank_below(uint64_t mask, int base = 0) {
+    return (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, (uint32_t)base));
 }
 
 // Value of `v` held by lane (lane ^ MASK), MASK a compile-time constant.  ANN_XOR_IMPL picks
