@@ -38,7 +38,7 @@
  * membership of a row matters to it; the order is fixed so that two implementations can
  * be compared entry by entry.
  *
- * Parity pins (tests/test_oracle_pins.py): detour counts against the boolean matrix
+ * Parity pins (tests/test_oracle_graph_pins.py): detour counts against the boolean matrix
  * product that defines two-hop reachability, a graph worked by hand, graphs without
  * two-hop routes, the transitive tournament's closed form, reverse lists against a
  * global lexicographic sort, and the invariants of the merged rows.
