@@ -90,8 +90,9 @@ extern "C" int ann_index_load(const ann_index_desc_t* desc, ann_index_t** out_ha
     const int64_t row_bytes = (int64_t)d.dim * elem_size(d.dtype);
     if (row_bytes % 16 != 0)
         return fail(ANN_EINVAL, "ann_index_load: a row of %lld bytes is not a multiple of 16", (long long)row_bytes);
-    if (d.row_stride_bytes < row_bytes || d.row_stride_bytes % 16 != 0)
-        return fail(ANN_EINVAL, "ann_index_load: row_stride_bytes = %lld (rows are %lld bytes; must be a multiple of 16)",
+    if (d.row_stride_bytes < row_bytes || d.row_stride_bytes % 16 != 0 || d.row_stride_bytes > INT32_MAX)
+        return fail(ANN_EINVAL,
+                    "ann_index_load: row_stride_bytes = %lld (rows are %lld bytes; must be a multiple of 16 below 2^31)",
                     (long long)d.row_stride_bytes, (long long)row_bytes);
     if (!aligned16(d.vectors)) return fail(ANN_EINVAL, "ann_index_load: vectors not 16-byte aligned");
     if (d.degree < 1 || d.degree > kMaxBatch) return fail(ANN_EINVAL, "ann_index_load: degree = %d outside 1..%d", d.degree, kMaxBatch);

@@ -212,6 +212,9 @@ struct BeamSearch {
 #else
         const uint64_t worst = this->worst;
 #endif
+        // the host keeps the stride below 2^31, so a row's address is one 32 x 32 -> 64 bit multiply-add
+        const uint8_t* const piece0 = row.lane_piece(p.vectors);
+        const uint32_t stride = (uint32_t)p.row_stride;
         int kept = 0;
         for (int j0 = 0; j0 < m; j0 += RPS * U) {
             u32x4 x[U][NCH];
@@ -222,14 +225,14 @@ struct BeamSearch {
                 const int j = j0 + u * RPS + grp;
                 const bool live = j < m;
                 id[u] = live ? cid[j] : 0u;
-                row.load_row(x[u], p.vectors + (int64_t)id[u] * p.row_stride, live);
+                row.load_row(x[u], piece0 + (uint64_t)id[u] * stride, live);
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 if (j0 + u * RPS >= m) break;
                 const int j = j0 + u * RPS + grp;
                 const uint32_t okey = row.key(x[u], lane);
-                const uint64_t packed = ((uint64_t)okey << 32) | ((uint64_t)id[u] << 1);
+                const uint64_t packed = ((uint64_t)okey << 32) | (uint64_t)(id[u] << 1);  // ids are below 2^31
                 const bool keep = j < m && row.lg == 0 && packed < worst;
                 const uint64_t b = __ballot(keep);
                 if (keep) ckey[rank_below(b, kept)] = packed;
@@ -394,9 +397,12 @@ struct BeamSearch {
             // parents: the first <= width unexpanded entries in list order
             int before = 0, total = 0;
             bool un[LPL];
+            uint32_t ex[LPL];  // the entries' expanded flags
 #pragma unroll
             for (int r = 0; r < LPL; ++r) {
-                un[r] = ((uint32_t)L[r] & 1u) == 0;
+                // taken in the 32-bit low word (the compiler otherwise widens the test to the whole key)
+                asm("v_and_b32 %0, 1, %1" : "=v"(ex[r]) : "v"((uint32_t)L[r]));
+                un[r] = ex[r] == 0;
                 const uint64_t b = __ballot(un[r]);
                 before = rank_below(b, before);
                 total += __builtin_popcountll(b);
@@ -408,7 +414,7 @@ struct BeamSearch {
                 const bool take = un[r] && before < np;
                 if (take) parents[before] = (uint32_t)L[r] >> 1;
                 L[r] |= (uint64_t)(take ? 1u : 0u);
-                before += un[r] ? 1 : 0;
+                before += (int)(ex[r] ^ 1u);
             }
             n_parents += np;
             if (n_table + np * p.degree > limit) reset_table();
@@ -423,7 +429,8 @@ struct BeamSearch {
                 nb[t] = -1;
                 if (s < nref) {
                     const int pi = (int)(((uint32_t)s * p.degree_inv) >> 20);
-                    nb[t] = ANN_GRAPH_LOAD(p.graph + (int64_t)parents[pi] * p.degree + (s - pi * p.degree));
+                    // unsigned 32 x 32 -> 64 bit: one multiply-add
+                    nb[t] = ANN_GRAPH_LOAD(p.graph + ((uint64_t)parents[pi] * (uint32_t)p.degree + (uint32_t)(s - pi * p.degree)));
                 }
             }
             m = 0;

@@ -43,7 +43,7 @@ __global__ void __launch_bounds__(64) route_kernel(const RouteParams p) {
         const int c = c0 + grp;
         const bool live = c < p.n_clusters;
         u32x4 x[NCH];
-        row.load_row(x, p.centroids + (int64_t)(live ? c : 0) * p.row_bytes, live);
+        row.load_row(x, row.lane_piece(p.centroids + (int64_t)(live ? c : 0) * p.row_bytes), live);
         const uint32_t okey = row.key(x, lane);
         uint64_t cand = live ? (((uint64_t)okey << 32) | (uint32_t)c) : kInfKey;
         if (__any(cand < best[kMaxRouteC - 1])) {

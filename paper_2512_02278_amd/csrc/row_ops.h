@@ -81,14 +81,16 @@ struct RowOps {
         }
     }
 
-    // Issues this lane's loads of the row that starts at `row` (rows the caller does
+    // This lane's first piece of the row that starts at `row`.
+    __device__ __forceinline__ const uint8_t* lane_piece(const uint8_t* row) const { return row + lg * 16; }
+
+    // Issues this lane's loads of the row whose lane_piece() is `piece` (rows the caller does
     // not want pass live = false and read nothing).
-    __device__ __forceinline__ void load_row(u32x4 (&x)[NCH], const uint8_t* row, bool live) const {
+    __device__ __forceinline__ void load_row(u32x4 (&x)[NCH], const uint8_t* piece, bool live) const {
 #pragma unroll
         for (int c = 0; c < NCH; ++c) {
             const bool ok = live && ((piece_ok >> c) & 1u);
-            x[c] = ok ? ANN_ROW_LOAD(reinterpret_cast<const u32x4*>(row + (c * G + lg) * 16))
-                      : u32x4{0, 0, 0, 0};
+            x[c] = ok ? ANN_ROW_LOAD(reinterpret_cast<const u32x4*>(piece + c * G * 16)) : u32x4{0, 0, 0, 0};
         }
     }
 

@@ -72,6 +72,7 @@ def test_load_and_free_roundtrip():
     (dict(dim=100, row_stride_bytes=112), ann.ANN_EINVAL),      # 100 bytes: not a multiple of 16
     (dict(row_stride_bytes=64), ann.ANN_EINVAL),                # stride below the row length
     (dict(row_stride_bytes=136), ann.ANN_EINVAL),               # stride not a multiple of 16
+    (dict(row_stride_bytes=1 << 31), ann.ANN_EINVAL),           # stride of 2^31 bytes or more
     (dict(vectors=FAKE + 8), ann.ANN_EINVAL),                   # misaligned
     (dict(degree=0), ann.ANN_EINVAL),
     (dict(n_entry=0), ann.ANN_EINVAL),
