@@ -100,7 +100,7 @@ struct BeamSearch {
     static constexpr int G = Row::G;
     static constexpr int NCH = Row::NCH;
     static constexpr int RPS = 64 / G;                                // rows per gather step
-    static constexpr int U = NCH >= 4 ? 1 : (NCH >= 2 ? 2 : 4);       // gather steps in flight
+    static constexpr int U = NCH >= 4 ? 1 : (NCH >= 2 ? 3 : 4);       // gather steps in flight
     static constexpr int BR = LPL >= 2 ? 2 : 1;                       // registers of a sort batch
     static constexpr int kInsertMax = ANN_INSERT_MAX;                 // at most this many new keys are inserted one by one
 
@@ -216,8 +216,12 @@ struct BeamSearch {
         const uint8_t* const piece0 = row.lane_piece(p.vectors);
         const uint32_t stride = (uint32_t)p.row_stride;
         int kept = 0;
+        u32x4 x[U][NCH];  // zeroed once: see reload_row
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int c = 0; c < NCH; ++c) x[u][c] = u32x4{0, 0, 0, 0};
         for (int j0 = 0; j0 < m; j0 += RPS * U) {
-            u32x4 x[U][NCH];
             uint32_t id[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
@@ -225,7 +229,7 @@ struct BeamSearch {
                 const int j = j0 + u * RPS + grp;
                 const bool live = j < m;
                 id[u] = live ? cid[j] : 0u;
-                row.load_row(x[u], piece0 + (uint64_t)id[u] * stride, live);
+                row.reload_row(x[u], piece0 + (uint64_t)id[u] * stride, live);
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) {

@@ -94,6 +94,15 @@ struct RowOps {
         }
     }
 
+    // The same for a buffer that is reused from row to row: a piece this lane does not load keeps what
+    // x held.  The caller zeroes x once (pieces beyond the row's end then stay zero for good) and
+    // ignores the key of a row it passed with live = false.
+    __device__ __forceinline__ void reload_row(u32x4 (&x)[NCH], const uint8_t* piece, bool live) const {
+#pragma unroll
+        for (int c = 0; c < NCH; ++c)
+            if (live && ((piece_ok >> c) & 1u)) x[c] = ANN_ROW_LOAD(reinterpret_cast<const u32x4*>(piece + c * G * 16));
+    }
+
     // Ordered key of the row whose pieces are in x; valid in every lane of the group.
     __device__ __forceinline__ uint32_t key(const u32x4 (&x)[NCH], int lane) const {
         if constexpr (DT == kU8) {
