@@ -219,10 +219,10 @@ def main() -> int:
     search_ms = event_ms(lambda: ann.ann_search(h, q, k, itopk, width, max_iters, out_ids=out_ids, out_dists=out_d,
                                                 routes=routes), args.steps)
     # the same kernel without the cluster-grouped execution order: every gather goes to HBM
-    os.environ["ANN_NO_CLUSTER_ORDER"] = "1"
+    ann.ann_index_set_option(h, ann.ANN_OPT_CLUSTER_ORDER_MIN_QUERIES, -1)
     ungrouped_ms = event_ms(lambda: ann.ann_search(h, q, k, itopk, width, max_iters, out_ids=out_ids, out_dists=out_d,
                                                    routes=routes), max(2, args.steps // 2))
-    del os.environ["ANN_NO_CLUSTER_ORDER"]
+    ann.ann_index_set_option(h, ann.ANN_OPT_CLUSTER_ORDER_MIN_QUERIES, 16384)
     counters = torch.zeros((nq, 4), dtype=torch.int32, device=dev)
     ann.ann_search(h, q, k, itopk, width, max_iters, out_ids=out_ids, out_dists=out_d, counters=counters)
     torch.cuda.synchronize()

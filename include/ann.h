@@ -87,6 +87,28 @@ typedef struct {
 int ann_index_load(const ann_index_desc_t* desc, ann_index_t** out_handle);
 
 /*
+ * Tuning and test hooks of a handle.  The defaults are what the measurements use; the options exist
+ * so that tests can force the rarely taken paths (a visited hash that overflows, a bitmap shorter
+ * than a cluster, the plain routing kernel) and so that a benchmark can time the search without
+ * the cluster-grouped execution order.  None of them changes a result (Sec. 3.2 "Stage 3" fixes what
+ * is computed; these only choose how).  Must not be called while a search on the handle is being
+ * enqueued by another thread.  Errors: ANN_EINVAL (unknown option, value out of range),
+ * ANN_EUNSUPPORTED (no kernel variant fits).
+ */
+enum {
+    ANN_OPT_CLUSTER_ORDER_MIN_QUERIES = 0, /* routed batches of at least this many queries run grouped by
+                                              cluster (default 16384); 0 = always, negative = never */
+    ANN_OPT_VISITED_WINDOW_BITS = 1,       /* bits of the exact visited bitmap over the routed clusters' id
+                                              ranges, 0 .. 131072 (default 8192; rounded up to 32); 0 = hash only */
+    ANN_OPT_VISITED_HASH_BITS_BIAS = 2,    /* -4 .. 4: log2 factor on the size of the visited hash (default 0);
+                                              the hash never gets smaller than the rounds need */
+    ANN_OPT_MATRIX_CORE_ROUTING = 3,       /* 0: route with the plain one-wavefront-per-query kernel (default 1) */
+    ANN_OPT_LANES_PER_ROW = 4              /* lanes that share one vector row in the gather, among the built
+                                              variants (4, 8 or 32); 0 = the default choice */
+};
+int ann_index_set_option(ann_index_t* handle, int option, int64_t value);
+
+/*
  * Enqueues the search of `nq` queries on `stream` and returns without waiting.
  *   queries    DEVICE, nq dense rows of `dim` elements of the index dtype, 16-byte aligned
  *   k          results per query, 1 <= k <= itopk
@@ -102,7 +124,9 @@ int ann_index_load(const ann_index_desc_t* desc, ann_index_t** out_handle);
  * routes; for batches of 16384 queries or more also nq + n_clusters int32 for the
  * cluster-grouped execution order) is allocated and released on `stream`.  On an
  * argument error nothing is launched and the outputs are untouched.  Calls on
- * different streams may share a handle.
+ * different streams may share a handle.  A route id outside [0, n_clusters) (only possible
+ * through ann_search_routed) names no cluster: it gives no entries, and a query whose routes
+ * all do so returns padding.
  */
 int ann_search(ann_index_t* handle, const void* queries, int64_t nq, int k, int itopk, int width, int max_iters,
                int32_t* out_ids, void* out_dists, void* stream);

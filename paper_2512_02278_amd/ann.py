@@ -17,13 +17,16 @@ LIB_PATH = os.path.join(_HERE, "libann.so")
 ANN_U8, ANN_F16, ANN_F32 = 0, 1, 2
 ANN_L2, ANN_IP = 0, 1
 ANN_ENTRY_UNIFORM, ANN_ENTRY_ROUTED = 0, 1
+(ANN_OPT_CLUSTER_ORDER_MIN_QUERIES, ANN_OPT_VISITED_WINDOW_BITS, ANN_OPT_VISITED_HASH_BITS_BIAS,
+ ANN_OPT_MATRIX_CORE_ROUTING, ANN_OPT_LANES_PER_ROW) = range(5)
 ANN_OK, ANN_EINVAL, ANN_EUNSUPPORTED, ANN_ENOMEM, ANN_EHIP = 0, -1, -2, -3, -4
 
 _DTYPES = {torch.uint8: ANN_U8, torch.float16: ANN_F16, torch.float32: ANN_F32}
 
 EXPORTS = ("ann_index_load", "ann_search", "ann_search_counters", "ann_search_routed", "ann_route", "ann_free",
            "ann_last_error", "ann_lds_bytes", "ann_calibration_copy", "ann_gather_vectors", "ann_merge_topk",
-           "ann_graph_prune", "ann_graph_optimize", "ann_graph_optimize_workspace_bytes", "ann_calibration_gather")
+           "ann_graph_prune", "ann_graph_optimize", "ann_graph_optimize_workspace_bytes", "ann_calibration_gather",
+           "ann_index_set_option")
 
 
 class ann_index_desc_t(ctypes.Structure):
@@ -63,6 +66,8 @@ def lib() -> ctypes.CDLL:
         L.ann_search_routed.restype = ctypes.c_int
         L.ann_route.argtypes = [vp, vp, i64, vp, vp]
         L.ann_route.restype = ctypes.c_int
+        L.ann_index_set_option.argtypes = [vp, i32, i64]
+        L.ann_index_set_option.restype = ctypes.c_int
         L.ann_free.argtypes = [vp]
         L.ann_free.restype = ctypes.c_int
         L.ann_last_error.argtypes = []
@@ -141,6 +146,10 @@ def ann_index_load(vectors: torch.Tensor, graph: torch.Tensor, metric: int = ANN
     h = ctypes.c_void_p()
     _check(lib().ann_index_load(ctypes.byref(d), ctypes.byref(h)))
     return Handle(h, (vectors, graph, centroids, cluster_offsets), vectors.dtype, vectors.shape[1], route_c)
+
+
+def ann_index_set_option(h: Handle, option: int, value: int) -> None:
+    _check(lib().ann_index_set_option(h.ptr, option, value))
 
 
 def _queries_ok(h: Handle, queries: torch.Tensor):

@@ -20,7 +20,7 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-u
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-I", INCLUDE, "-I", CSRC]
 
 
-EXTRA = os.environ.get("ANN_EXTRA_FLAGS", "").split()  # e.g. -DNAME=VALUE switches while tuning
+EXTRA = []  # further hipcc flags for this build (command line: python -m paper_2512_02278_amd.build -DNAME=VALUE ...)
 # the routing kernels read every matrix result with the vector ALU: keep the accumulators in VGPRs
 PER_FILE = {"route_mfma_u8.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"], "route_mfma.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
 
@@ -60,7 +60,8 @@ def _compile(src: str) -> str:
     return obj
 
 
-def build(jobs: int = 8) -> str:
+def build(jobs: int = 8, extra_flags=()) -> str:
+    EXTRA[:] = list(extra_flags)
     os.makedirs(OBJ, exist_ok=True)
     srcs = sorted(glob.glob(os.path.join(CSRC, "*.hip")))
     with concurrent.futures.ThreadPoolExecutor(max_workers=jobs) as ex:
@@ -77,4 +78,4 @@ def build(jobs: int = 8) -> str:
 
 
 if __name__ == "__main__":
-    print(build())
+    print(build(extra_flags=sys.argv[1:]))

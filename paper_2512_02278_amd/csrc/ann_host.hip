@@ -6,6 +6,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 
 #include "ann.h"
@@ -65,13 +66,27 @@ struct ann_index {
     ann_index_desc_t d;
     int row_bytes;
     const ann::RowVariant* variant;
-    int hash_bits_bias;  // ANN_HASH_BITS_BIAS: extra (or fewer) bits for the visited hash, for tuning
-    int window_bits;     // ANN_WINDOW_BITS: size of the visited bitmap over the routed clusters' ids
+    // set by ann_index_set_option:
+    int hash_bits_bias;       // extra (or fewer) bits for the visited hash
+    int window_bits;          // size of the visited bitmap over the routed clusters' ids
+    int64_t cluster_order_min;  // batches of at least this many queries run grouped by cluster; < 0: never
+    bool matrix_core_routing;
     int32_t* centroid_bias;  // DEVICE, owned: per-centroid term of the uint8 d=128 matrix-core routing, or null
     void* route_bias;        // DEVICE, owned: the same for the general matrix-core routing, or null
 };
 
 using namespace ann;
+
+// The smallest variant that covers the row; among equals the one with fewer lanes per row (more rows
+// per instruction).  lanes != 0 restricts the choice to variants with that many lanes per row.
+static const RowVariant* pick_variant(int dtype, int metric, int64_t row_bytes, int lanes) {
+    const RowVariant* best = nullptr;
+    for (const RowVariant& v : kRowVariants)
+        if (v.dtype == dtype && v.metric == metric && (int64_t)v.g * v.nch * 16 >= row_bytes && (lanes == 0 || v.g == lanes) &&
+            (!best || v.g * v.nch < best->g * best->nch || (v.g * v.nch == best->g * best->nch && v.g < best->g)))
+            best = &v;
+    return best;
+}
 
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -107,16 +122,7 @@ extern "C" int ann_index_load(const ann_index_desc_t* desc, ann_index_t** out_ha
         if (d.route_c < 1 || d.route_c > d.n_clusters || d.route_c > kMaxRouteC)
             return fail(ANN_EINVAL, "ann_index_load: route_c = %d outside 1..min(n_clusters, %d)", d.route_c, kMaxRouteC);
     }
-    // the smallest variant that covers the row; among equals the one with fewer lanes per row
-    // (more rows per instruction).  ANN_ROW_LANES pins the lanes per row, for tuning.
-    const char* pin = getenv("ANN_ROW_LANES");
-    const int pin_g = pin ? atoi(pin) : 0;
-    const RowVariant* best = nullptr;
-    for (const RowVariant& v : kRowVariants)
-        if (v.dtype == d.dtype && v.metric == d.metric && (int64_t)v.g * v.nch * 16 >= row_bytes &&
-            (pin_g == 0 || v.g == pin_g) &&
-            (!best || v.g * v.nch < best->g * best->nch || (v.g * v.nch == best->g * best->nch && v.g < best->g)))
-            best = &v;
+    const RowVariant* best = pick_variant(d.dtype, d.metric, row_bytes, 0);
     if (!best) return fail(ANN_EUNSUPPORTED, "ann_index_load: no kernel variant for rows of %lld bytes of this dtype", (long long)row_bytes);
     ann_index* h = new (std::nothrow) ann_index;
     if (!h) return fail(ANN_ENOMEM, "ann_index_load: out of host memory");
@@ -124,16 +130,13 @@ extern "C" int ann_index_load(const ann_index_desc_t* desc, ann_index_t** out_ha
     h->d = d;
     h->row_bytes = (int)row_bytes;
     h->variant = best;
-    const char* bias = getenv("ANN_HASH_BITS_BIAS");
-    h->hash_bits_bias = bias ? atoi(bias) : 0;
-    const char* wb = getenv("ANN_WINDOW_BITS");
-    int window_bits = wb ? atoi(wb) : kDefaultWindowBits;
-    if (window_bits < 0) window_bits = 0;
-    if (window_bits > kMaxWindowBits) window_bits = kMaxWindowBits;
-    h->window_bits = d.entry_mode == ANN_ENTRY_ROUTED ? (window_bits + 31) / 32 * 32 : 0;
+    h->hash_bits_bias = 0;
+    h->window_bits = d.entry_mode == ANN_ENTRY_ROUTED ? kDefaultWindowBits : 0;
+    h->cluster_order_min = kMinQueriesForClusterOrder;
+    h->matrix_core_routing = true;
     h->centroid_bias = nullptr;
     h->route_bias = nullptr;
-    const bool mfma_route = d.entry_mode == ANN_ENTRY_ROUTED && !getenv("ANN_NO_MFMA_ROUTE");
+    const bool mfma_route = d.entry_mode == ANN_ENTRY_ROUTED;
     if (mfma_route && !(d.dtype == ANN_U8 && d.dim == 128) && row_bytes % 32 == 0) {
         hipError_t e = hipMalloc(&h->route_bias, 4 * (size_t)route_mfma_padded(d.n_clusters));
         if (e == hipSuccess)
@@ -222,22 +225,88 @@ extern "C" int64_t ann_lds_bytes(ann_index_t* h, int itopk, int width) {
     return rc != ANN_OK ? rc : (int64_t)plan.lds_bytes;
 }
 
-extern "C" int ann_route(ann_index_t* h, const void* queries, int64_t nq, int32_t* out_clusters, void* stream) {
-    if (!h || h->magic != kMagic) return fail(ANN_EINVAL, "ann_route: not a live handle");
-    if (h->d.entry_mode != ANN_ENTRY_ROUTED) return fail(ANN_EINVAL, "ann_route: the index has no centroids");
-    if (nq < 0) return fail(ANN_EINVAL, "ann_route: nq = %lld", (long long)nq);
-    if (nq == 0) return ANN_OK;
-    if (!queries || !out_clusters) return fail(ANN_EINVAL, "ann_route: null argument");
-    if (!aligned16(queries)) return fail(ANN_EINVAL, "ann_route: queries not 16-byte aligned");
-    if (h->centroid_bias || h->route_bias) {
+extern "C" int ann_index_set_option(ann_index_t* h, int option, int64_t value) {
+    if (!h || h->magic != kMagic) return fail(ANN_EINVAL, "ann_index_set_option: not a live handle");
+    switch (option) {
+        case ANN_OPT_CLUSTER_ORDER_MIN_QUERIES:
+            h->cluster_order_min = value;
+            return ANN_OK;
+        case ANN_OPT_VISITED_WINDOW_BITS:
+            if (value < 0 || value > kMaxWindowBits)
+                return fail(ANN_EINVAL, "ann_index_set_option: visited window of %lld bits outside 0..%d", (long long)value, kMaxWindowBits);
+            h->window_bits = h->d.entry_mode == ANN_ENTRY_ROUTED ? (int)((value + 31) / 32 * 32) : 0;
+            return ANN_OK;
+        case ANN_OPT_VISITED_HASH_BITS_BIAS:
+            if (value < -4 || value > 4) return fail(ANN_EINVAL, "ann_index_set_option: hash bits bias %lld outside -4..4", (long long)value);
+            h->hash_bits_bias = (int)value;
+            return ANN_OK;
+        case ANN_OPT_MATRIX_CORE_ROUTING:
+            h->matrix_core_routing = value != 0;
+            return ANN_OK;
+        case ANN_OPT_LANES_PER_ROW: {
+            const RowVariant* v = pick_variant(h->d.dtype, h->d.metric, h->row_bytes, (int)value);
+            if (value < 0 || value > 64 || !v)
+                return fail(ANN_EUNSUPPORTED, "ann_index_set_option: no kernel variant with %lld lanes per row for this index", (long long)value);
+            h->variant = v;
+            return ANN_OK;
+        }
+        default:
+            return fail(ANN_EINVAL, "ann_index_set_option: unknown option %d", option);
+    }
+}
+
+namespace {
+
+// Where a call's temporaries come from: stream-ordered allocations (released on the same stream when
+// the call has enqueued its work), or consecutive pieces of a buffer the call was given.
+struct Workspace {
+    hipStream_t stream;
+    char* fixed = nullptr;  // null: allocate
+    size_t fixed_bytes = 0, used = 0;
+    void* owned[4];
+    int n_owned = 0;
+
+    explicit Workspace(hipStream_t s) : stream(s) {}
+    Workspace(hipStream_t s, void* buffer, size_t bytes) : stream(s), fixed(static_cast<char*>(buffer)), fixed_bytes(bytes) {}
+    Workspace(const Workspace&) = delete;
+
+    // DEVICE memory of `bytes` bytes, 256-byte aligned, or null (hipErrorOutOfMemory in *err).
+    void* take(size_t bytes, hipError_t* err) {
+        *err = hipSuccess;
+        if (fixed) {
+            const size_t at = (used + 255) / 256 * 256;
+            if (at + bytes > fixed_bytes) {
+                *err = hipErrorOutOfMemory;
+                return nullptr;
+            }
+            used = at + bytes;
+            return fixed + at;
+        }
+        void* p = nullptr;
+        if (n_owned == 4) {
+            *err = hipErrorOutOfMemory;
+            return nullptr;
+        }
+        *err = hipMallocAsync(&p, bytes, stream);
+        if (*err != hipSuccess) return nullptr;
+        owned[n_owned++] = p;
+        return p;
+    }
+    ~Workspace() {
+        for (int i = 0; i < n_owned; ++i) (void)hipFreeAsync(owned[i], stream);
+    }
+};
+
+int route_impl(ann_index_t* h, const void* queries, int64_t nq, int32_t* out_clusters, Workspace& ws) {
+    hipStream_t st = ws.stream;
+    if (h->matrix_core_routing && (h->centroid_bias || h->route_bias)) {
         // matrix-core routing; small batches cut the centroid range into slices and merge them
-        hipStream_t st = static_cast<hipStream_t>(stream);
         const int slices = h->centroid_bias ? route_mfma_u8_slices(h->d.n_clusters, nq) : route_mfma_slices(h->d.n_clusters, nq);
         uint64_t* partial = nullptr;
         if (slices > 1) {
-            const hipError_t e = hipMallocAsync(reinterpret_cast<void**>(&partial),
-                                                sizeof(uint64_t) * (size_t)nq * slices * h->d.route_c, st);
-            if (e != hipSuccess) return fail(ANN_ENOMEM, "ann_route: scratch allocation failed: %s", hipGetErrorString(e));
+            hipError_t e;
+            partial = static_cast<uint64_t*>(ws.take(sizeof(uint64_t) * (size_t)nq * slices * h->d.route_c, &e));
+            if (!partial) return fail(ANN_ENOMEM, "ann_route: no scratch memory for %d centroid slices: %s", slices, hipGetErrorString(e));
         }
         const uint8_t* cen = static_cast<const uint8_t*>(h->d.centroids);
         const uint8_t* qs = static_cast<const uint8_t*>(queries);
@@ -246,7 +315,6 @@ extern "C" int ann_route(ann_index_t* h, const void* queries, int64_t nq, int32_
                                                     out_clusters, partial, slices, st)
                              : launch_route_mfma(h->d.dtype, h->d.metric, h->d.route_c, cen, h->route_bias, h->d.n_clusters,
                                                  h->row_bytes, qs, nq, out_clusters, partial, slices, st);
-        if (partial) (void)hipFreeAsync(partial, st);
         if (e != hipSuccess) return fail(ANN_EHIP, "ann_route: launch failed: %s", hipGetErrorString(e));
         return ANN_OK;
     }
@@ -259,10 +327,23 @@ extern "C" int ann_route(ann_index_t* h, const void* queries, int64_t nq, int32_
         rp.nq = nq - q0 < kMaxQueriesPerLaunch ? nq - q0 : kMaxQueriesPerLaunch;
         rp.route_c = h->d.route_c;
         rp.out = out_clusters + q0 * h->d.route_c;
-        const hipError_t e = h->variant->route(rp, static_cast<hipStream_t>(stream));
+        const hipError_t e = h->variant->route(rp, st);
         if (e != hipSuccess) return fail(ANN_EHIP, "ann_route: launch failed: %s", hipGetErrorString(e));
     }
     return ANN_OK;
+}
+
+}  // namespace
+
+extern "C" int ann_route(ann_index_t* h, const void* queries, int64_t nq, int32_t* out_clusters, void* stream) {
+    if (!h || h->magic != kMagic) return fail(ANN_EINVAL, "ann_route: not a live handle");
+    if (h->d.entry_mode != ANN_ENTRY_ROUTED) return fail(ANN_EINVAL, "ann_route: the index has no centroids");
+    if (nq < 0) return fail(ANN_EINVAL, "ann_route: nq = %lld", (long long)nq);
+    if (nq == 0) return ANN_OK;
+    if (!queries || !out_clusters) return fail(ANN_EINVAL, "ann_route: null argument");
+    if (!aligned16(queries)) return fail(ANN_EINVAL, "ann_route: queries not 16-byte aligned");
+    Workspace ws(static_cast<hipStream_t>(stream));
+    return route_impl(h, queries, nq, out_clusters, ws);
 }
 
 namespace {
@@ -270,8 +351,8 @@ namespace {
 // Checks the arguments of a search and launches it; `route` is null for uniform entries.
 int search_impl(ann_index_t* h, const void* queries, int64_t nq, const int32_t* route, bool route_given, int k,
                 int itopk, int width, int max_iters, int32_t* out_ids, void* out_dists, int32_t* out_counters,
-                hipStream_t stream) {
-    if (!h || h->magic != kMagic) return fail(ANN_EINVAL, "ann_search: not a live handle");
+                Workspace& ws) {
+    hipStream_t stream = ws.stream;
     if (nq < 0) return fail(ANN_EINVAL, "ann_search: nq = %lld", (long long)nq);
     if (k < 1 || k > itopk) return fail(ANN_EINVAL, "ann_search: k = %d outside 1..itopk (%d)", k, itopk);
     if (max_iters < 0) return fail(ANN_EINVAL, "ann_search: max_iters = %d", max_iters);
@@ -284,32 +365,24 @@ int search_impl(ann_index_t* h, const void* queries, int64_t nq, const int32_t* 
     if (!queries || !out_ids || !out_dists || (route_given && !route)) return fail(ANN_EINVAL, "ann_search: null argument");
     if (!aligned16(queries)) return fail(ANN_EINVAL, "ann_search: queries not 16-byte aligned");
 
-    int32_t* scratch = nullptr;
     if (h->d.entry_mode == ANN_ENTRY_ROUTED && !route_given) {
-        const hipError_t e = hipMallocAsync(reinterpret_cast<void**>(&scratch), sizeof(int32_t) * (size_t)nq * h->d.route_c, stream);
-        if (e != hipSuccess) return fail(ANN_ENOMEM, "ann_search: scratch allocation failed: %s", hipGetErrorString(e));
-        const int r = ann_route(h, queries, nq, scratch, stream);
-        if (r != ANN_OK) {
-            (void)hipFreeAsync(scratch, stream);
-            return r;
-        }
-        route = scratch;
+        hipError_t e;
+        int32_t* routes = static_cast<int32_t*>(ws.take(sizeof(int32_t) * (size_t)nq * h->d.route_c, &e));
+        if (!routes) return fail(ANN_ENOMEM, "ann_search: no scratch memory for the routes: %s", hipGetErrorString(e));
+        const int r = route_impl(h, queries, nq, routes, ws);
+        if (r != ANN_OK) return r;
+        route = routes;
     }
     // routed batches that are large enough run grouped by cluster, for cache reuse
     int32_t* order = nullptr;
-    if (h->d.entry_mode == ANN_ENTRY_ROUTED && nq >= kMinQueriesForClusterOrder && nq <= 2147483647ll &&
-        !getenv("ANN_NO_CLUSTER_ORDER")) {
-        hipError_t e = hipMallocAsync(reinterpret_cast<void**>(&order), sizeof(int32_t) * ((size_t)nq + h->d.n_clusters), stream);
-        if (e == hipSuccess)
-            e = launch_cluster_order(route, h->d.route_c, nq, h->d.n_clusters, order + nq, order, stream);
-        if (e != hipSuccess) {
-            if (order) (void)hipFreeAsync(order, stream);
-            if (scratch) (void)hipFreeAsync(scratch, stream);
-            return fail(ANN_ENOMEM, "ann_search: preparing the execution order failed: %s", hipGetErrorString(e));
-        }
+    if (h->d.entry_mode == ANN_ENTRY_ROUTED && h->cluster_order_min >= 0 && nq >= h->cluster_order_min && nq <= 2147483647ll) {
+        hipError_t e;
+        order = static_cast<int32_t*>(ws.take(sizeof(int32_t) * ((size_t)nq + h->d.n_clusters), &e));
+        if (!order) return fail(ANN_ENOMEM, "ann_search: no scratch memory for the execution order: %s", hipGetErrorString(e));
+        e = launch_cluster_order(route, h->d.route_c, nq, h->d.n_clusters, order + nq, order, stream);
+        if (e != hipSuccess) return fail(ANN_EHIP, "ann_search: launching the execution-order kernels failed: %s", hipGetErrorString(e));
     }
 
-    int result = ANN_OK;
     for (int64_t q0 = 0; q0 < nq; q0 += kMaxQueriesPerLaunch) {
         const int64_t cnt = nq - q0 < kMaxQueriesPerLaunch ? nq - q0 : kMaxQueriesPerLaunch;
         SearchParams p;
@@ -335,6 +408,7 @@ int search_impl(ann_index_t* h, const void* queries, int64_t nq, const int32_t* 
         p.route = route;
         p.cluster_offsets = h->d.cluster_offsets;
         p.route_c = h->d.route_c;
+        p.n_clusters = h->d.n_clusters;
         p.hash_bits = plan.hash_bits;
         p.window_bits = h->window_bits;
         p.cap = plan.cap;
@@ -343,14 +417,9 @@ int search_impl(ann_index_t* h, const void* queries, int64_t nq, const int32_t* 
         p.out_counters = out_counters;
         p.order = order;
         const hipError_t e = h->variant->search(p, plan.list_variant, (unsigned)(8 * p.q_per_xcd), plan.lds_bytes, stream);
-        if (e != hipSuccess) {
-            result = fail(ANN_EHIP, "ann_search: launch failed: %s", hipGetErrorString(e));
-            break;
-        }
+        if (e != hipSuccess) return fail(ANN_EHIP, "ann_search: launch failed: %s", hipGetErrorString(e));
     }
-    if (order) (void)hipFreeAsync(order, stream);
-    if (scratch) (void)hipFreeAsync(scratch, stream);
-    return result;
+    return ANN_OK;
 }
 
 }  // namespace
@@ -358,15 +427,17 @@ int search_impl(ann_index_t* h, const void* queries, int64_t nq, const int32_t* 
 extern "C" int ann_search_counters(ann_index_t* h, const void* queries, int64_t nq, int k, int itopk, int width,
                                    int max_iters, int32_t* out_ids, void* out_dists, int32_t* out_counters,
                                    void* stream) {
-    return search_impl(h, queries, nq, nullptr, false, k, itopk, width, max_iters, out_ids, out_dists, out_counters,
-                       static_cast<hipStream_t>(stream));
+    if (!h || h->magic != kMagic) return fail(ANN_EINVAL, "ann_search: not a live handle");
+    Workspace ws(static_cast<hipStream_t>(stream));
+    return search_impl(h, queries, nq, nullptr, false, k, itopk, width, max_iters, out_ids, out_dists, out_counters, ws);
 }
 
 extern "C" int ann_search_routed(ann_index_t* h, const void* queries, int64_t nq, const int32_t* routes, int k,
                                  int itopk, int width, int max_iters, int32_t* out_ids, void* out_dists,
                                  int32_t* out_counters, void* stream) {
-    return search_impl(h, queries, nq, routes, true, k, itopk, width, max_iters, out_ids, out_dists, out_counters,
-                       static_cast<hipStream_t>(stream));
+    if (!h || h->magic != kMagic) return fail(ANN_EINVAL, "ann_search_routed: not a live handle");
+    Workspace ws(static_cast<hipStream_t>(stream));
+    return search_impl(h, queries, nq, routes, true, k, itopk, width, max_iters, out_ids, out_dists, out_counters, ws);
 }
 
 extern "C" int ann_search(ann_index_t* h, const void* queries, int64_t nq, int k, int itopk, int width, int max_iters,

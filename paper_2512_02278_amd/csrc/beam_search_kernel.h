@@ -25,21 +25,6 @@
 
 #include "row_ops.h"
 
-#ifndef ANN_NT_GRAPH
-#define ANN_NT_GRAPH 0
-#endif
-#if ANN_NT_GRAPH
-#define ANN_GRAPH_LOAD(p) __builtin_nontemporal_load(p)
-#else
-#define ANN_GRAPH_LOAD(p) (*(p))
-#endif
-#ifndef ANN_INSERT_MAX
-#define ANN_INSERT_MAX 8
-#endif
-#ifndef ANN_MIN_WAVES
-#define ANN_MIN_WAVES 7
-#endif
-
 namespace ann {
 
 struct SearchParams {
@@ -59,6 +44,7 @@ struct SearchParams {
     const int32_t* route;            // nq * route_c nearest clusters (routed mode)
     const int64_t* cluster_offsets;  // routed mode
     int32_t route_c;
+    int32_t n_clusters;   // routed mode: a route id outside [0, n_clusters) names no cluster (no window, no entries)
     int32_t hash_bits;    // visited hash has 1 << hash_bits slots
     int32_t window_bits;  // bits of the visited bitmap (multiple of 32; 0 = none)
     int32_t cap;        // most candidates one round can produce, multiple of 64
@@ -102,7 +88,7 @@ struct BeamSearch {
     static constexpr int RPS = 64 / G;                                // rows per gather step
     static constexpr int U = NCH >= 4 ? 1 : (NCH >= 2 ? 3 : 4);       // gather steps in flight
     static constexpr int BR = LPL >= 2 ? 2 : 1;                       // registers of a sort batch
-    static constexpr int kInsertMax = ANN_INSERT_MAX;                 // at most this many new keys are inserted one by one
+    static constexpr int kInsertMax = 8;                // at most this many new keys are inserted one by one
 
     const SearchParams& p;
     int lane;
@@ -207,11 +193,7 @@ struct BeamSearch {
     // ckey[0..returned count).
     __device__ __forceinline__ int score(int m) {
         const int grp = lane / G;
-#ifdef ANN_NO_WORST_FILTER
-        const uint64_t worst = kInfKey;
-#else
         const uint64_t worst = this->worst;
-#endif
         // the host keeps the stride below 2^31, so a row's address is one 32 x 32 -> 64 bit multiply-add
         const uint8_t* const piece0 = row.lane_piece(p.vectors);
         const uint32_t stride = (uint32_t)p.row_stride;
@@ -353,9 +335,10 @@ struct BeamSearch {
             uint32_t bit = 0;
             for (int w = 0; w < p.route_c; ++w) {
                 const int32_t c = p.route[qi * p.route_c + w];
-                const int64_t lo = p.cluster_offsets[c], hi = p.cluster_offsets[c + 1];
+                const bool known = (uint32_t)c < (uint32_t)p.n_clusters;
+                const int64_t lo = known ? p.cluster_offsets[c] : 0, hi = known ? p.cluster_offsets[c + 1] : 0;
                 const uint32_t room = (uint32_t)p.window_bits - bit;
-                const uint32_t size = (uint64_t)(hi - lo) < room ? (uint32_t)(hi - lo) : room;
+                const uint32_t size = hi <= lo ? 0u : (uint64_t)(hi - lo) < room ? (uint32_t)(hi - lo) : room;
                 if (lane == 0) {
                     wtab[3 * w] = (uint32_t)lo;
                     wtab[3 * w + 1] = size;
@@ -384,7 +367,8 @@ struct BeamSearch {
                     e = (int32_t)(z % (uint64_t)p.n);
                 } else {
                     const int32_t c = p.route[qi * p.route_c + (j % p.route_c)];
-                    const int64_t lo = p.cluster_offsets[c], hi = p.cluster_offsets[c + 1];
+                    const bool known = (uint32_t)c < (uint32_t)p.n_clusters;
+                    const int64_t lo = known ? p.cluster_offsets[c] : 0, hi = known ? p.cluster_offsets[c + 1] : 0;
                     if (hi > lo) e = (int32_t)(lo + (int64_t)(z % (uint64_t)(hi - lo)));
                 }
             }
@@ -434,7 +418,7 @@ struct BeamSearch {
                 if (s < nref) {
                     const int pi = (int)(((uint32_t)s * p.degree_inv) >> 20);
                     // unsigned 32 x 32 -> 64 bit: one multiply-add
-                    nb[t] = ANN_GRAPH_LOAD(p.graph + ((uint64_t)parents[pi] * (uint32_t)p.degree + (uint32_t)(s - pi * p.degree)));
+                    nb[t] = p.graph[(uint64_t)parents[pi] * (uint32_t)p.degree + (uint32_t)(s - pi * p.degree)];
                 }
             }
             m = 0;
@@ -471,7 +455,7 @@ struct BeamSearch {
 // The small uint8 variants are asked to fit 7 wavefronts per SIMD (72 vector registers; 8 would need spills):
 // with about 5.5 KB of LDS per query that is also what a compute unit's LDS holds, 28 queries in flight.
 template <class Row, int LPL, int CPL>
-__global__ void __launch_bounds__(64, (ANN_MIN_WAVES > 1 && Row::kDtype == kU8 && LPL <= 4 && CPL <= 2) ? ANN_MIN_WAVES : 1)
+__global__ void __launch_bounds__(64, (Row::kDtype == kU8 && LPL <= 4 && CPL <= 2) ? 7 : 1)
     beam_search_kernel(const SearchParams p) {
     extern __shared__ uint32_t lds[];
     const int64_t b = blockIdx.x;

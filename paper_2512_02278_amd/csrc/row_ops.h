@@ -15,16 +15,8 @@
 #include "wave.h"
 
 // Row and graph loads are ordinary cached loads: queries of one cluster run next to each other and
-// re-read each other's rows from L2 / the memory-side cache; the non-temporal hint (1) costs a
-// quarter of the throughput with the cluster-grouped order and a tenth even without it.
-#ifndef ANN_NT_ROWS
-#define ANN_NT_ROWS 0
-#endif
-#if ANN_NT_ROWS
-#define ANN_ROW_LOAD(p) __builtin_nontemporal_load(p)
-#else
-#define ANN_ROW_LOAD(p) (*(p))
-#endif
+// re-read each other's rows from L2 / the memory-side cache (a non-temporal hint costs a quarter of
+// the throughput with the cluster-grouped order and a tenth even without it).
 
 namespace ann {
 
@@ -90,7 +82,7 @@ struct RowOps {
 #pragma unroll
         for (int c = 0; c < NCH; ++c) {
             const bool ok = live && ((piece_ok >> c) & 1u);
-            x[c] = ok ? ANN_ROW_LOAD(reinterpret_cast<const u32x4*>(piece + c * G * 16)) : u32x4{0, 0, 0, 0};
+            x[c] = ok ? *reinterpret_cast<const u32x4*>(piece + c * G * 16) : u32x4{0, 0, 0, 0};
         }
     }
 
@@ -100,7 +92,7 @@ struct RowOps {
     __device__ __forceinline__ void reload_row(u32x4 (&x)[NCH], const uint8_t* piece, bool live) const {
 #pragma unroll
         for (int c = 0; c < NCH; ++c)
-            if (live && ((piece_ok >> c) & 1u)) x[c] = ANN_ROW_LOAD(reinterpret_cast<const u32x4*>(piece + c * G * 16));
+            if (live && ((piece_ok >> c) & 1u)) x[c] = *reinterpret_cast<const u32x4*>(piece + c * G * 16);
     }
 
     // Ordered key of the row whose pieces are in x; valid in every lane of the group.

@@ -18,10 +18,16 @@ __global__ void __launch_bounds__(256) fill_zero_kernel(int32_t* p, int64_t n) {
     for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) p[i] = 0;
 }
 
+// A route id outside [0, n_clusters) names no cluster; such a query is filed under cluster 0, so
+// that it still gets a place in the order (it runs, finds no entries and returns padding).
+__device__ __forceinline__ int32_t bucket_of(int32_t c, int n_clusters) {
+    return (uint32_t)c < (uint32_t)n_clusters ? c : 0;
+}
+
 __global__ void __launch_bounds__(256) cluster_histogram_kernel(const int32_t* route, int route_c, int64_t nq,
-                                                                int32_t* counts) {
+                                                                int n_clusters, int32_t* counts) {
     for (int64_t q = (int64_t)blockIdx.x * 256 + threadIdx.x; q < nq; q += (int64_t)gridDim.x * 256)
-        atomicAdd(&counts[route[q * route_c]], 1);
+        atomicAdd(&counts[bucket_of(route[q * route_c], n_clusters)], 1);
 }
 
 // counts[c] <- number of queries routed to clusters below c (one workgroup, any n).
@@ -49,9 +55,9 @@ __global__ void __launch_bounds__(1024) exclusive_scan_kernel(int32_t* counts, i
 }
 
 __global__ void __launch_bounds__(256) cluster_scatter_kernel(const int32_t* route, int route_c, int64_t nq,
-                                                              int32_t* offsets, int32_t* order) {
+                                                              int n_clusters, int32_t* offsets, int32_t* order) {
     for (int64_t q = (int64_t)blockIdx.x * 256 + threadIdx.x; q < nq; q += (int64_t)gridDim.x * 256)
-        order[atomicAdd(&offsets[route[q * route_c]], 1)] = (int32_t)q;
+        order[atomicAdd(&offsets[bucket_of(route[q * route_c], n_clusters)], 1)] = (int32_t)q;
 }
 
 hipError_t launch_cluster_order(const int32_t* route, int route_c, int64_t nq, int n_clusters, int32_t* counts,
@@ -59,9 +65,9 @@ hipError_t launch_cluster_order(const int32_t* route, int route_c, int64_t nq, i
     const unsigned blocks = (unsigned)((nq + 255) / 256 < 4096 ? (nq + 255) / 256 : 4096);
     hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)((n_clusters + 255) / 256)), dim3(256), 0, stream, counts,
                        (int64_t)n_clusters);
-    hipLaunchKernelGGL(cluster_histogram_kernel, dim3(blocks), dim3(256), 0, stream, route, route_c, nq, counts);
+    hipLaunchKernelGGL(cluster_histogram_kernel, dim3(blocks), dim3(256), 0, stream, route, route_c, nq, n_clusters, counts);
     hipLaunchKernelGGL(exclusive_scan_kernel, dim3(1), dim3(1024), 0, stream, counts, n_clusters);
-    hipLaunchKernelGGL(cluster_scatter_kernel, dim3(blocks), dim3(256), 0, stream, route, route_c, nq, counts, order);
+    hipLaunchKernelGGL(cluster_scatter_kernel, dim3(blocks), dim3(256), 0, stream, route, route_c, nq, n_clusters, counts, order);
     return hipGetLastError();
 }
 

@@ -22,50 +22,32 @@ __device__ __forceinline__ int rank_below(uint64_t mask, int base = 0) {
     return (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, (uint32_t)base));
 }
 
-// Value of `v` held by lane (lane ^ MASK), MASK a compile-time constant.  ANN_XOR_IMPL picks
-// the mechanism: 0 = ds_bpermute everywhere; 1 = DPP moves inside a row of 16 lanes (quad
-// permutes, half-row and row mirrors, rotate by 8) and v_permlane16/32_swap across rows;
-// 2 (default, fastest measured) = DPP inside a row, ds_bpermute across rows: the search loop
-// is bound by vector-ALU issue, and the LDS crossbar takes the cross-row moves off the VALU;
-// 3 = ds_swizzle / ds_bpermute only.
+// Value of `v` held by lane (lane ^ MASK), MASK a compile-time constant: DPP moves inside a
+// row of 16 lanes (quad permutes, half-row and row mirrors, rotate by 8), ds_bpermute across
+// rows.  The search loop is bound by vector-ALU issue, and the LDS crossbar takes the
+// cross-row moves off the vector ALU.
 template <int CTRL>
 __device__ __forceinline__ uint32_t dpp_move(uint32_t v) {
     // every lane has a source inside its row for the controls used here, so the "old" value is dead
     return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xf, 0xf, true);
 }
-#ifndef ANN_XOR_IMPL
-#define ANN_XOR_IMPL 2
-#endif
 template <int MASK>
 __device__ __forceinline__ uint32_t xor_lane(uint32_t v, int lane) {
     static_assert(MASK >= 0 && MASK < 64, "lane mask");
-#if ANN_XOR_IMPL == 0
-    return (uint32_t)__builtin_amdgcn_ds_bpermute((lane ^ MASK) << 2, (int)v);
-#elif ANN_XOR_IMPL == 2
-    if constexpr ((MASK & 48) != 0) return (uint32_t)__builtin_amdgcn_ds_bpermute((lane ^ MASK) << 2, (int)v);
-#elif ANN_XOR_IMPL == 3
-    // LDS crossbar, no VALU work: ds_swizzle in bit-mask mode inside 32 lanes, ds_bpermute beyond
-    if constexpr (MASK < 32) return (uint32_t)__builtin_amdgcn_ds_swizzle((int)v, 0x1F | (MASK << 10));
-    else return (uint32_t)__builtin_amdgcn_ds_bpermute((lane ^ MASK) << 2, (int)v);
-#endif
-    constexpr int low = MASK & 15;
-    if constexpr (low == 1) v = dpp_move<0xB1>(v);        // quad_perm [1,0,3,2]
-    else if constexpr (low == 2) v = dpp_move<0x4E>(v);   // quad_perm [2,3,0,1]
-    else if constexpr (low == 3) v = dpp_move<0x1B>(v);   // quad_perm [3,2,1,0]
-    else if constexpr (low == 4) v = dpp_move<0x1B>(dpp_move<0x141>(v));  // (i ^ 7) ^ 3
-    else if constexpr (low == 7) v = dpp_move<0x141>(v);  // row_half_mirror
-    else if constexpr (low == 8) v = dpp_move<0x128>(v);  // row_ror:8
-    else if constexpr (low == 15) v = dpp_move<0x140>(v); // row_mirror
-    else static_assert(low == 0, "unsupported lane mask");
-    if constexpr ((MASK & 16) != 0) {
-        auto r = __builtin_amdgcn_permlane16_swap(v, v, false, false);
-        v = (lane & 16) ? r[0] : r[1];
+    if constexpr ((MASK & 48) != 0) {
+        return (uint32_t)__builtin_amdgcn_ds_bpermute((lane ^ MASK) << 2, (int)v);
+    } else {
+        constexpr int low = MASK & 15;
+        if constexpr (low == 1) v = dpp_move<0xB1>(v);        // quad_perm [1,0,3,2]
+        else if constexpr (low == 2) v = dpp_move<0x4E>(v);   // quad_perm [2,3,0,1]
+        else if constexpr (low == 3) v = dpp_move<0x1B>(v);   // quad_perm [3,2,1,0]
+        else if constexpr (low == 4) v = dpp_move<0x1B>(dpp_move<0x141>(v));  // (i ^ 7) ^ 3
+        else if constexpr (low == 7) v = dpp_move<0x141>(v);  // row_half_mirror
+        else if constexpr (low == 8) v = dpp_move<0x128>(v);  // row_ror:8
+        else if constexpr (low == 15) v = dpp_move<0x140>(v); // row_mirror
+        else static_assert(low == 0, "unsupported lane mask");
+        return v;
     }
-    if constexpr ((MASK & 32) != 0) {
-        auto r = __builtin_amdgcn_permlane32_swap(v, v, false, false);
-        v = (lane & 32) ? r[0] : r[1];
-    }
-    return v;
 }
 template <int MASK>
 __device__ __forceinline__ uint64_t xor_lane64(uint64_t v, int lane) {

@@ -62,6 +62,40 @@ def test_load_and_free_roundtrip():
     assert ann.lib().ann_free(None) == ann.ANN_OK
 
 
+def test_set_option_checks_its_arguments():
+    L = ann.lib()
+    rc, h = load(desc(entry_mode=1, centroids=FAKE, cluster_offsets=FAKE, n_clusters=40, route_c=2, dim=100, dtype=ann.ANN_F32,
+                      row_stride_bytes=400))  # 400-byte rows: no matrix-core routing, so nothing touches a device
+    assert rc == ann.ANN_OK
+    base = L.ann_lds_bytes(h, 128, 4)
+    assert L.ann_index_set_option(h, ann.ANN_OPT_VISITED_WINDOW_BITS, 0) == ann.ANN_OK
+    assert L.ann_lds_bytes(h, 128, 4) == base - 8192 // 8 + 4 * (1 << 9)      # no bitmap; the hash gets one more bit
+    assert L.ann_index_set_option(h, ann.ANN_OPT_VISITED_WINDOW_BITS, 100) == ann.ANN_OK   # rounded up to 128 bits
+    assert L.ann_lds_bytes(h, 128, 4) == base - 8192 // 8 + 128 // 8
+    assert L.ann_index_set_option(h, ann.ANN_OPT_VISITED_WINDOW_BITS, (1 << 17) + 1) == ann.ANN_EINVAL
+    assert L.ann_index_set_option(h, ann.ANN_OPT_VISITED_WINDOW_BITS, -1) == ann.ANN_EINVAL
+    assert L.ann_index_set_option(h, ann.ANN_OPT_VISITED_HASH_BITS_BIAS, 5) == ann.ANN_EINVAL
+    assert L.ann_index_set_option(h, ann.ANN_OPT_VISITED_HASH_BITS_BIAS, -1) == ann.ANN_OK
+    assert L.ann_index_set_option(h, ann.ANN_OPT_CLUSTER_ORDER_MIN_QUERIES, -1) == ann.ANN_OK
+    assert L.ann_index_set_option(h, ann.ANN_OPT_MATRIX_CORE_ROUTING, 0) == ann.ANN_OK
+    assert L.ann_index_set_option(h, ann.ANN_OPT_LANES_PER_ROW, 32) == ann.ANN_OK
+    assert L.ann_index_set_option(h, ann.ANN_OPT_LANES_PER_ROW, 8) == ann.ANN_EUNSUPPORTED   # 8 lanes x 3 pieces hold 384 bytes
+    assert L.ann_index_set_option(h, ann.ANN_OPT_LANES_PER_ROW, 5) == ann.ANN_EUNSUPPORTED
+    assert L.ann_index_set_option(h, ann.ANN_OPT_LANES_PER_ROW, 0) == ann.ANN_OK
+    assert L.ann_index_set_option(h, 99, 0) == ann.ANN_EINVAL
+    assert "unknown option" in ann.ann_last_error()
+    assert L.ann_index_set_option(None, ann.ANN_OPT_MATRIX_CORE_ROUTING, 0) == ann.ANN_EINVAL
+    assert L.ann_free(h) == ann.ANN_OK
+
+
+def test_product_sources_read_no_environment_variables():
+    """Nothing outside the C ABI steers the library: its sources never call getenv."""
+    import glob
+
+    for path in glob.glob(os.path.join(ROOT, "paper_2512_02278_amd", "csrc", "*")):
+        assert "getenv" not in open(path).read(), path
+
+
 @pytest.mark.parametrize("kw,code", [
     (dict(vectors=None), ann.ANN_EINVAL),
     (dict(graph=None), ann.ANN_EINVAL),

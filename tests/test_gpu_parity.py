@@ -26,7 +26,7 @@ def torch_cuda():
 
 
 def gpu_search(torch, x, g, q, k, itopk, width, max_iters, metric=0, n_entry=32, entry_mode=0, seed=0, centroids=None,
-               offsets=None, route_c=0, want_counters=True):
+               offsets=None, route_c=0, want_counters=True, options=None):
     from paper_2512_02278_amd import ann
 
     dev = "cuda:0"
@@ -42,6 +42,8 @@ def gpu_search(torch, x, g, q, k, itopk, width, max_iters, metric=0, n_entry=32,
     ot = None if offsets is None else torch.from_numpy(np.ascontiguousarray(offsets, dtype=np.int64)).to(dev)
     h = ann.ann_index_load(xt, gt, metric=metric, n_entry=n_entry, entry_mode=entry_mode, seed=seed, centroids=ct,
                            cluster_offsets=ot, route_c=route_c)
+    for opt, value in (options or {}).items():
+        ann.ann_index_set_option(h, opt, value)
     cnt = torch.zeros((q.shape[0], 4), dtype=torch.int32, device=dev) if want_counters else None
     ids, dists = ann.ann_search(h, qt, k, itopk, width, max_iters, counters=cnt)
     torch.cuda.synchronize()
@@ -205,22 +207,23 @@ def test_uint8_dims_and_padded_rows(oracle, torch_cuda, dim):
     check_exact(oracle, torch_cuda, x, g, q, 10, 64, 2, 40, n_entry=8, seed=1)
 
 
-def test_small_visited_hash_forces_resets(oracle, torch_cuda, monkeypatch):
+def test_small_visited_hash_forces_resets(oracle, torch_cuda):
     """Without the bitmap and with the smallest hash the kernel forgets visited nodes every
     few rounds; the result must not change, only more rows are gathered."""
     rng = np.random.default_rng(77)
     x, cen, off = clustered(rng, 8000, 128, "u8", n_centres=4)
     g = knn_graph(x, 32)
     q = queries_near(rng, x, 200, "u8")
-    monkeypatch.setenv("ANN_HASH_BITS_BIAS", "-1")
-    monkeypatch.setenv("ANN_WINDOW_BITS", "0")
+    from paper_2512_02278_amd import ann
+
     gc, oc = check_exact(oracle, torch_cuda, x, g, q, 10, 128, 4, 100, n_entry=32, seed=2, entry_mode=1,
-                         centroids=cen, offsets=off, route_c=1)
+                         centroids=cen, offsets=off, route_c=1,
+                         options={ann.ANN_OPT_VISITED_HASH_BITS_BIAS: -1, ann.ANN_OPT_VISITED_WINDOW_BITS: 0})
     assert gc[:, 3].max() >= 1 and (gc[:, 1] > oc["n_dist"]).any()
 
 
 @pytest.mark.parametrize("window_bits,route_c", [(8192, 1), (8192, 3), (512, 2), (96, 1)])
-def test_visited_bitmap_windows(oracle, torch_cuda, monkeypatch, window_bits, route_c):
+def test_visited_bitmap_windows(oracle, torch_cuda, window_bits, route_c):
     """The visited bitmap covers the routed clusters' id ranges; ids beyond it (other
     clusters, or a bitmap shorter than the clusters) go to the hash.  Whole, partial
     and tiny bitmaps give the oracle's answer; a bitmap that covers the query's
@@ -229,14 +232,16 @@ def test_visited_bitmap_windows(oracle, torch_cuda, monkeypatch, window_bits, ro
     x, cen, off = clustered(rng, 8000, 128, "u8", n_centres=4, spread=40.0)  # clusters overlap: edges cross
     g = knn_graph(x, 32)
     q = queries_near(rng, x, 200, "u8")
-    monkeypatch.setenv("ANN_WINDOW_BITS", str(window_bits))
+    from paper_2512_02278_amd import ann
+
     gc, oc = check_exact(oracle, torch_cuda, x, g, q, 10, 128, 4, 100, n_entry=32, seed=2, entry_mode=1,
-                         centroids=cen, offsets=off, route_c=route_c)
+                         centroids=cen, offsets=off, route_c=route_c,
+                         options={ann.ANN_OPT_VISITED_WINDOW_BITS: window_bits})
     if window_bits == 8192 and route_c == 3:
         assert (gc[:, 1] - oc["n_dist"]).mean() < 0.05 * oc["n_dist"].mean()
 
 
-def test_cluster_grouped_execution_order(oracle, torch_cuda, monkeypatch):
+def test_cluster_grouped_execution_order(oracle, torch_cuda):
     """Batches of 16384 queries or more run grouped by routed cluster; a query keeps its position
     (and so its entries), so the answers are those of the oracle and of the ungrouped run."""
     rng = np.random.default_rng(91)
@@ -246,9 +251,41 @@ def test_cluster_grouped_execution_order(oracle, torch_cuda, monkeypatch):
     kw = dict(n_entry=32, seed=6, entry_mode=1, centroids=cen, offsets=off, route_c=2)
     gc, oc = check_exact(oracle, torch_cuda, x, g, q, 10, 64, 2, 60, **kw)
     grouped = gpu_search(torch_cuda, x, g, q, 10, 64, 2, 60, **kw)
-    monkeypatch.setenv("ANN_NO_CLUSTER_ORDER", "1")
-    plain = gpu_search(torch_cuda, x, g, q, 10, 64, 2, 60, **kw)
+    from paper_2512_02278_amd import ann
+
+    plain = gpu_search(torch_cuda, x, g, q, 10, 64, 2, 60, options={ann.ANN_OPT_CLUSTER_ORDER_MIN_QUERIES: -1}, **kw)
     assert all(np.array_equal(a, b) for a, b in zip(grouped, plain))
+
+
+def test_route_ids_outside_the_clusters_are_ignored(oracle, torch_cuda):
+    """ann_search_routed takes the routes from the caller.  A route id outside [0, n_clusters) names no
+    cluster: the query gets no entries from it (padding if all its routes are such), nothing is read
+    out of bounds, and the other queries of the batch answer as the oracle does - also when the batch
+    is large enough to run grouped by cluster."""
+    from paper_2512_02278_amd import ann
+
+    torch = torch_cuda
+    rng = np.random.default_rng(92)
+    x, cen, off = clustered(rng, 20_000, 128, "u8", n_centres=40)
+    g = knn_graph_blocked(x, off, 32)
+    for nq in (300, 17_000):
+        q = queries_near(rng, x, nq, "u8")
+        ix = oracle.Index(x, g, n_entry=32, entry_mode=1, seed=6, centroids=cen, cluster_offsets=off, route_c=1)
+        oi, od, _ = oracle.search(ix, q, 10, 64, 2, 60)
+        h = ann.ann_index_load(torch.from_numpy(x).cuda(), torch.from_numpy(g).cuda(), n_entry=32, entry_mode=1, seed=6,
+                               centroids=torch.from_numpy(cen).cuda(), cluster_offsets=torch.from_numpy(off).cuda(), route_c=1)
+        qt = torch.from_numpy(q).cuda()
+        routes = ann.ann_route(h, qt)
+        bad = rng.random(nq) < 0.1
+        bad[:4] = True
+        routes[torch.from_numpy(bad).cuda(), 0] = torch.from_numpy(
+            rng.choice(np.array([-1, 40, 41, 2**31 - 1, -2**31], np.int64), int(bad.sum())).astype(np.int32)).cuda()
+        gi, gd = ann.ann_search(h, qt, 10, 64, 2, 60, routes=routes)
+        torch.cuda.synchronize()
+        ann.ann_free(h)
+        gi, gd = gi.cpu().numpy(), gd.cpu().numpy()
+        assert (gi[bad] == -1).all() and (gd[bad] == np.iinfo(np.int32).max).all()
+        assert np.array_equal(gi[~bad], oi[~bad]) and np.array_equal(gd[~bad], od[~bad])
 
 
 def test_edge_cases(oracle, torch_cuda):
@@ -292,7 +329,7 @@ def test_float_parity(oracle, torch_cuda, dt, dim, metric, itopk, width, degree,
                                                         (5, 5, 64, 128), (4097, 3, 300, 128), (333, 2, 130, 64),
                                                         (200, 8, 65, 256), (70, 1, 40, 32),
                                                         (16640, 2, 300, 128), (16384, 1, 1000, 128), (2049, 3, 5, 128)])
-def test_uint8_matrix_core_routing_is_exact(oracle, torch_cuda, monkeypatch, metric, n_clusters, route_c, nq, dim):
+def test_uint8_matrix_core_routing_is_exact(oracle, torch_cuda, metric, n_clusters, route_c, nq, dim):
     """uint8 d=128 routing runs on the matrix cores (shifted to int8, exact int32 sums) and must give
     the oracle's clusters in the oracle's order, ties by cluster index included; the plain kernel
     (matrix cores switched off) must give the same."""
@@ -310,10 +347,9 @@ def test_uint8_matrix_core_routing_is_exact(oracle, torch_cuda, monkeypatch, met
     gt = torch.zeros((64, 4), dtype=torch.int32, device="cuda")
     off = torch.zeros(n_clusters + 1, dtype=torch.int64, device="cuda")
     for no_mfma in (False, True):
-        if no_mfma:
-            monkeypatch.setenv("ANN_NO_MFMA_ROUTE", "1")
         h = ann.ann_index_load(xt, gt, metric=metric, entry_mode=1, centroids=torch.from_numpy(cen).cuda(),
                                cluster_offsets=off, route_c=route_c)
+        ann.ann_index_set_option(h, ann.ANN_OPT_MATRIX_CORE_ROUTING, 0 if no_mfma else 1)
         got = ann.ann_route(h, torch.from_numpy(q).cuda()).cpu().numpy()
         ann.ann_free(h)
         assert np.array_equal(got, want), (no_mfma, np.argwhere(got != want)[:5].tolist())
@@ -321,7 +357,7 @@ def test_uint8_matrix_core_routing_is_exact(oracle, torch_cuda, monkeypatch, met
 
 @pytest.mark.parametrize("no_mfma", [False, True])
 @pytest.mark.parametrize("metric", [0, 1])
-def test_route_matches_oracle(oracle, torch_cuda, monkeypatch, metric, no_mfma):
+def test_route_matches_oracle(oracle, torch_cuda, metric, no_mfma):
     """Routing of float data (matrix cores: fp32 accumulation of q.c plus |c|^2; plain kernel:
     (q-c)^2 in fp32) against the oracle's double-precision keys: the same clusters except where
     two centroids are within rounding of each other, and never a cluster that is worse than the
@@ -330,8 +366,6 @@ def test_route_matches_oracle(oracle, torch_cuda, monkeypatch, metric, no_mfma):
 
     torch = torch_cuda
     rng = np.random.default_rng(3)
-    if no_mfma:
-        monkeypatch.setenv("ANN_NO_MFMA_ROUTE", "1")
     for dt, dim, nq in (("u8", 128, 100), ("f32", 96, 333), ("f16", 768, 100), ("f32", 8, 70), ("f16", 16, 129)):
         x, cen, off = clustered(rng, 2000, dim, dt, n_centres=300)
         q = queries_near(rng, x, nq, dt)
@@ -340,6 +374,7 @@ def test_route_matches_oracle(oracle, torch_cuda, monkeypatch, metric, no_mfma):
         gt = torch.zeros((2000, 4), dtype=torch.int32, device="cuda")
         h = ann.ann_index_load(xt, gt, metric=metric, entry_mode=1, centroids=ct,
                                cluster_offsets=torch.from_numpy(off).cuda(), route_c=4)
+        ann.ann_index_set_option(h, ann.ANN_OPT_MATRIX_CORE_ROUTING, 0 if no_mfma else 1)
         got = ann.ann_route(h, torch.from_numpy(q).cuda()).cpu().numpy()
         ann.ann_free(h)
         if dt == "u8":
