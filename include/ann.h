@@ -132,6 +132,28 @@ int ann_search(ann_index_t* handle, const void* queries, int64_t nq, int k, int 
                int32_t* out_ids, void* out_dists, void* stream);
 
 /*
+ * ann_search for callers that cannot allocate device memory: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments, same results, same kernels; the
+ * temporaries (routes, execution order, routing partials) live in a device array of
+ * ANN_STATIC_SCRATCH_BYTES that is part of the library's code object (every GPU the library runs on
+ * holds it until the process ends).  The call allocates and frees nothing.  Its first call on a
+ * device looks up that device's address of the array (one runtime query, no allocation): make one
+ * call outside any capture first.
+ * Limit: the temporaries of one call, each rounded up to 256 bytes -
+ *     4*nq*route_c                       routes
+ *   + 8*nq*slices*route_c                routing partials of small batches (slices <= 64, nq*slices <= 131072)
+ *   + 4*(nq + n_clusters)                execution order, for batches that run grouped by cluster
+ * - must fit: e.g. 1M queries at route_c = 1 take 8.1 MB.  A larger batch gives ANN_EUNSUPPORTED
+ * and launches nothing; an index with uniform entries needs no temporaries at all.
+ * All calls on one GPU share the array: calls that overlap in time on one GPU (different streams or
+ * threads) race and give wrong results; calls on one stream are safe.  The array keeps the last
+ * call's contents; everything that must start at zero is cleared by the call itself.
+ */
+#define ANN_STATIC_SCRATCH_BYTES (32 * 1024 * 1024)
+int ann_search_static(ann_index_t* handle, const void* queries, int64_t nq, int k, int itopk, int width, int max_iters,
+                      int32_t* out_ids, void* out_dists, void* stream);
+
+/*
  * Same as ann_search, and additionally writes four int32 per query to
  * out_counters (DEVICE, nq*4, may be NULL): expansion rounds, keys computed
  * (vector rows gathered), graph rows read, visited-table resets.

@@ -19,6 +19,7 @@ ANN_L2, ANN_IP = 0, 1
 ANN_ENTRY_UNIFORM, ANN_ENTRY_ROUTED = 0, 1
 (ANN_OPT_CLUSTER_ORDER_MIN_QUERIES, ANN_OPT_VISITED_WINDOW_BITS, ANN_OPT_VISITED_HASH_BITS_BIAS,
  ANN_OPT_MATRIX_CORE_ROUTING, ANN_OPT_LANES_PER_ROW) = range(5)
+ANN_STATIC_SCRATCH_BYTES = 32 * 1024 * 1024
 ANN_OK, ANN_EINVAL, ANN_EUNSUPPORTED, ANN_ENOMEM, ANN_EHIP = 0, -1, -2, -3, -4
 
 _DTYPES = {torch.uint8: ANN_U8, torch.float16: ANN_F16, torch.float32: ANN_F32}
@@ -26,7 +27,7 @@ _DTYPES = {torch.uint8: ANN_U8, torch.float16: ANN_F16, torch.float32: ANN_F32}
 EXPORTS = ("ann_index_load", "ann_search", "ann_search_counters", "ann_search_routed", "ann_route", "ann_free",
            "ann_last_error", "ann_lds_bytes", "ann_calibration_copy", "ann_gather_vectors", "ann_merge_topk",
            "ann_graph_prune", "ann_graph_optimize", "ann_graph_optimize_workspace_bytes", "ann_calibration_gather",
-           "ann_index_set_option")
+           "ann_index_set_option", "ann_search_static")
 
 
 class ann_index_desc_t(ctypes.Structure):
@@ -60,6 +61,8 @@ def lib() -> ctypes.CDLL:
         L.ann_index_load.restype = ctypes.c_int
         L.ann_search.argtypes = [vp, vp, i64, i32, i32, i32, i32, vp, vp, vp]
         L.ann_search.restype = ctypes.c_int
+        L.ann_search_static.argtypes = [vp, vp, i64, i32, i32, i32, i32, vp, vp, vp]
+        L.ann_search_static.restype = ctypes.c_int
         L.ann_search_counters.argtypes = [vp, vp, i64, i32, i32, i32, i32, vp, vp, vp, vp]
         L.ann_search_counters.restype = ctypes.c_int
         L.ann_search_routed.argtypes = [vp, vp, i64, vp, i32, i32, i32, i32, vp, vp, vp, vp]
@@ -191,6 +194,21 @@ def ann_search(h: Handle, queries: torch.Tensor, k: int, itopk: int, width: int,
                                        _dev_ptr(out_ids, "out_ids"), _dev_ptr(out_dists, "out_dists"),
                                        _dev_ptr(counters, "counters"), _stream(stream))
     _check(rc)
+    return out_ids, out_dists
+
+
+def ann_search_static(h: Handle, queries: torch.Tensor, k: int, itopk: int, width: int, max_iters: int,
+                      out_ids: torch.Tensor, out_dists: torch.Tensor, stream=None):
+    """ann_search with the library's static scratch: the caller passes every buffer, nothing is allocated."""
+    _queries_ok(h, queries)
+    nq = queries.shape[0]
+    dd = torch.int32 if h.dtype == torch.uint8 else torch.float32
+    if out_ids.dtype != torch.int32 or out_dists.dtype != dd or out_ids.numel() != nq * k or out_dists.numel() != nq * k:
+        raise ValueError("out_ids / out_dists have the wrong dtype or size")
+    if not (out_ids.is_contiguous() and out_dists.is_contiguous()):
+        raise ValueError("outputs must be contiguous")
+    _check(lib().ann_search_static(h.ptr, _dev_ptr(queries, "queries"), nq, k, itopk, width, max_iters,
+                                   _dev_ptr(out_ids, "out_ids"), _dev_ptr(out_dists, "out_dists"), _stream(stream)))
     return out_ids, out_dists
 
 

@@ -261,19 +261,21 @@ namespace {
 // the call has enqueued its work), or consecutive pieces of a buffer the call was given.
 struct Workspace {
     hipStream_t stream;
-    char* fixed = nullptr;  // null: allocate
+    bool allocates;         // false: only pieces of `fixed`
+    char* fixed = nullptr;
     size_t fixed_bytes = 0, used = 0;
     void* owned[4];
     int n_owned = 0;
 
-    explicit Workspace(hipStream_t s) : stream(s) {}
-    Workspace(hipStream_t s, void* buffer, size_t bytes) : stream(s), fixed(static_cast<char*>(buffer)), fixed_bytes(bytes) {}
+    explicit Workspace(hipStream_t s) : stream(s), allocates(true) {}
+    Workspace(hipStream_t s, void* buffer, size_t bytes)
+        : stream(s), allocates(false), fixed(static_cast<char*>(buffer)), fixed_bytes(bytes) {}
     Workspace(const Workspace&) = delete;
 
     // DEVICE memory of `bytes` bytes, 256-byte aligned, or null (hipErrorOutOfMemory in *err).
     void* take(size_t bytes, hipError_t* err) {
         *err = hipSuccess;
-        if (fixed) {
+        if (!allocates) {
             const size_t at = (used + 255) / 256 * 256;
             if (at + bytes > fixed_bytes) {
                 *err = hipErrorOutOfMemory;
@@ -443,6 +445,70 @@ extern "C" int ann_search_routed(ann_index_t* h, const void* queries, int64_t nq
 extern "C" int ann_search(ann_index_t* h, const void* queries, int64_t nq, int k, int itopk, int width, int max_iters,
                           int32_t* out_ids, void* out_dists, void* stream) {
     return ann_search_counters(h, queries, nq, k, itopk, width, max_iters, out_ids, out_dists, nullptr, stream);
+}
+
+// ---------------------------------------------------------------------------------------------
+// ann_search_static: the same search with its temporaries in a device array that is part of the
+// library's code object, for callers that cannot allocate.
+namespace {
+
+constexpr size_t kStaticScratchBytes = (size_t)ANN_STATIC_SCRATCH_BYTES;
+// Host code must not use this name as an address: it is a host-side stand-in.  The device address is
+// asked for once per device (static_scratch_of_current_device) and that pointer is what kernels get.
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_static_mutex;
+void* g_static_ptr[kMaxDevices];  // per device: where that device holds its copy of `scratch`
+
+int static_scratch_of_current_device(void** out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(ANN_EHIP, "ann_search_static: hipGetDevice failed: %s", hipGetErrorString(e));
+    if (dev < 0 || dev >= kMaxDevices) return fail(ANN_EUNSUPPORTED, "ann_search_static: device %d outside 0..%d", dev, kMaxDevices - 1);
+    std::lock_guard<std::mutex> lock(g_static_mutex);
+    if (!g_static_ptr[dev]) {
+        void* ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !ptr)
+            return fail(ANN_EHIP, "ann_search_static: hipGetSymbolAddress failed: %s", hipGetErrorString(e));
+        g_static_ptr[dev] = ptr;
+    }
+    *out = g_static_ptr[dev];
+    return ANN_OK;
+}
+
+size_t padded256(size_t bytes) { return (bytes + 255) / 256 * 256; }
+
+// Bytes of temporaries a whole ann_search call of nq queries takes (what Workspace::take hands out).
+size_t search_scratch_bytes(const ann_index_t* h, int64_t nq) {
+    if (h->d.entry_mode != ANN_ENTRY_ROUTED || nq <= 0) return 0;
+    size_t need = padded256(sizeof(int32_t) * (size_t)nq * h->d.route_c);
+    if (h->matrix_core_routing && (h->centroid_bias || h->route_bias)) {
+        const int slices = h->centroid_bias ? route_mfma_u8_slices(h->d.n_clusters, nq) : route_mfma_slices(h->d.n_clusters, nq);
+        if (slices > 1) need += padded256(sizeof(uint64_t) * (size_t)nq * slices * h->d.route_c);
+    }
+    if (h->cluster_order_min >= 0 && nq >= h->cluster_order_min) need += padded256(sizeof(int32_t) * ((size_t)nq + h->d.n_clusters));
+    return need;
+}
+
+}  // namespace
+
+extern "C" int ann_search_static(ann_index_t* h, const void* queries, int64_t nq, int k, int itopk, int width, int max_iters,
+                                 int32_t* out_ids, void* out_dists, void* stream) {
+    if (!h || h->magic != kMagic) return fail(ANN_EINVAL, "ann_search_static: not a live handle");
+    const size_t need = search_scratch_bytes(h, nq);
+    if (need > kStaticScratchBytes)
+        return fail(ANN_EUNSUPPORTED,
+                    "ann_search_static: %lld queries need %zu bytes of temporaries, the static scratch holds %zu; split the batch",
+                    (long long)nq, need, kStaticScratchBytes);
+    void* base = nullptr;
+    if (need > 0) {
+        const int rc = static_scratch_of_current_device(&base);
+        if (rc != ANN_OK) return rc;
+    }
+    Workspace ws(static_cast<hipStream_t>(stream), base, need > 0 ? kStaticScratchBytes : 0);
+    return search_impl(h, queries, nq, nullptr, false, k, itopk, width, max_iters, out_ids, out_dists, nullptr, ws);
 }
 
 extern "C" int ann_gather_vectors(ann_index_t* h, const int32_t* ids, int64_t count, void* out_vectors, void* stream) {

@@ -88,6 +88,19 @@ def test_set_option_checks_its_arguments():
     assert L.ann_free(h) == ann.ANN_OK
 
 
+def test_static_scratch_size_in_header_and_binding_agree():
+    text = open(os.path.join(ROOT, "include", "ann.h")).read()
+    m = re.search(r"#define\s+ANN_STATIC_SCRATCH_BYTES\s+\(([^)]*)\)", text)
+    assert m and eval(m.group(1)) == ann.ANN_STATIC_SCRATCH_BYTES
+    L = ann.lib()
+    rc, h = load(desc())
+    # argument errors come before any device work; an empty batch launches nothing
+    assert L.ann_search_static(h, FAKE, 0, 10, 64, 1, 5, FAKE, FAKE, None) == ann.ANN_OK
+    assert L.ann_search_static(h, FAKE, 5, 0, 64, 1, 5, FAKE, FAKE, None) == ann.ANN_EINVAL
+    assert L.ann_search_static(None, FAKE, 5, 10, 64, 1, 5, FAKE, FAKE, None) == ann.ANN_EINVAL
+    assert L.ann_free(h) == ann.ANN_OK
+
+
 def test_product_sources_read_no_environment_variables():
     """Nothing outside the C ABI steers the library: its sources never call getenv."""
     import glob
