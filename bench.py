@@ -2,25 +2,41 @@
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--nq N]
 
-A step is one ann_search call (routing + beam search, every stage of the hot path)
-over one batch of synthetic queries that already sits in HBM.  The default workload
-is the 100M-vector uint8 partition ("one GPU's tenth of a billion-scale SIFT-like
+A step is one ann_search call (routing + execution order + beam search: every stage of the
+hot path) over one batch of synthetic queries that already sits in HBM.  The default
+workload is the 100M-vector uint8 partition ("one GPU's tenth of a billion-scale SIFT-like
 index").  Prints ONE JSON line; progress goes to stderr.
 
-The line carries: queries/s at the smallest itopk whose recall@10 reaches 0.95,
-recall, bytes per query (algorithmic, from the oracle's counters; actual, from the
-kernel's), the roofline of the beam-search kernel (HBM), a batch-size sweep, and the
-CPU oracle timed on this machine's host cores on a sample of the same batch, which is
-also checked bit for bit against the GPU's answers.
+The line carries: queries/s at the smallest itopk whose recall@k, less two standard errors,
+reaches 0.95 on 10 000 exactly solved queries; bytes per query (algorithmic, from the oracle's
+counters; gathered, from the kernel's); the roofline of the beam-search kernel; a batch-size
+sweep; and the CPU oracle timed on this machine's host cores on a sample of the same batch, which
+is also checked bit for bit against the GPU's answers.
 
-"value" is measured on the workload's own graph (the cluster-restricted kNN graph).
-Where the workload names a longer kNN list to start from, "optimized_graph" adds the
-same measurement on the graph that ann_graph_optimize builds from it at the same
-degree (build time, recall, queries/s, sampled rows checked against the oracle).
+Roofline.  The timed step runs the batch grouped by cluster, so most gathers hit L2 and the
+kernel is bound by vector-ALU instruction issue, not by HBM: "roofline" reports that resource
+(issued vector instructions x 64 lanes per second against 256 CUs x 4 SIMDs x 16 lanes x
+2.4 GHz), with the HBM view of the same launch ("hbm": measured L2<->fabric traffic / kernel
+time) and the same kernel in drawn order ("drawn_order": every gather goes to HBM, algorithmic
+bytes / kernel time against the 8 TB/s peak) beside it.  Instruction and byte counts come from
+rocprofv3 --pmc runs of `bench.py --profile` (summaries under profiles/); they are used only if
+the kernel sources they were taken on are the ones this run uses (a hash of the sources is
+stored with them), otherwise the fields are null and "roofline" falls back to the drawn-order
+HBM figure.
+
+"value" is measured on the workload's own graph (the cluster-restricted kNN graph).  Where
+the workload names a longer kNN list to start from, "optimized_graph" adds the same
+measurement on the graph that ann_graph_optimize builds from it at the same degree.
+
+--profile runs only what the counters are for (a few searches in each configuration, the graph
+construction, a copy of known size) with fixed --itopk / --opt-itopk and prints which launch is
+which; it is the program the rocprofv3 commands in profiles/ run.
 """
 from __future__ import annotations
 
 import argparse
+import glob
+import hashlib
 import json
 import os
 import sys
@@ -31,11 +47,17 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E, published peak
+# Vector-ALU issue: 256 compute units x 4 SIMDs x 16 lanes x 2.4 GHz lane-instructions per second (a wave64
+# instruction occupies its SIMD for 4 cycles); the published 157.3 TFLOP/s fp32 figure is this x 2 (FMA) x 2 (packed).
+VALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
+RECALL_TARGET = 0.95
+N_TRUTH = 10_000
 
 WORKLOADS = {
     # name: generator settings and search parameters (benchmark configs)
     "sift100m": dict(kind="sift", n=100_000_000, centres=16384, dim=128, degree=32, nq=1_000_000, k=10, width=4,
-                     max_iters=200, itopk_sweep=(128, 144, 160, 176, 184, 192, 208, 224, 256), sweep=(1_000, 10_000, 100_000, 1_000_000),
+                     max_iters=200, itopk_sweep=(128, 144, 160, 176, 184, 192, 200, 208, 224, 256),
+                     sweep=(1_000, 10_000, 100_000, 1_000_000),
                      optimize_from=64, opt_itopk_sweep=(96, 104, 112, 120, 128, 144, 160, 184),
                      text="100M x 128 uint8 SIFT-like partition, 16384 centres, degree-32 cluster-restricted kNN graph"),
     "sift1m": dict(kind="sift", n=1_000_000, centres=1000, dim=128, degree=32, nq=10_000, k=10, width=4, max_iters=100,
@@ -64,6 +86,33 @@ def log(msg: str) -> None:
     print(f"[bench {time.strftime('%H:%M:%S')}] {msg}", file=sys.stderr, flush=True)
 
 
+def sources_sha() -> str:
+    """Hash of everything the kernels are compiled from: counters taken on other sources are not this build's."""
+    h = hashlib.sha256()
+    base = os.path.join(ROOT, "paper_2512_02278_amd")
+    for path in sorted(glob.glob(os.path.join(base, "csrc", "*")) + [os.path.join(base, "build.py")]):
+        h.update(os.path.basename(path).encode())
+        h.update(open(path, "rb").read())
+    return h.hexdigest()[:16]
+
+
+def read_profile(kernel: str, workload: str) -> dict:
+    """`key = value` lines of the committed rocprofv3 --pmc summary of this kernel and workload (profiles/)."""
+    out = {}
+    try:
+        for ln in open(os.path.join(ROOT, "profiles", f"{kernel}_{workload}_pmc.txt")):
+            key, sep, val = ln.partition(" = ")
+            if sep and key and " " not in key.strip():
+                val = val.strip()
+                try:
+                    out[key.strip()] = float(val)
+                except ValueError:
+                    out[key.strip()] = val
+    except OSError:
+        pass
+    return out
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -74,6 +123,9 @@ def main() -> int:
     ap.add_argument("--oracle-seconds", type=float, default=15.0, help="wall-clock aim for the CPU oracle sample")
     ap.add_argument("--no-oracle", action="store_true", help="skip the CPU baseline and the sampled parity check")
     ap.add_argument("--no-optimized-graph", action="store_true", help="skip the optimized-graph measurement")
+    ap.add_argument("--itopk", type=int, default=0, help="fix the list size instead of choosing it by recall")
+    ap.add_argument("--opt-itopk", type=int, default=0, help="the same for the optimized graph")
+    ap.add_argument("--profile", action="store_true", help="only the launches the profiler's counters are for")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build covers one GPU's partition; it has no multi-GPU path, run with --gpus 1",
@@ -93,6 +145,7 @@ def main() -> int:
     w = WORKLOADS[args.workload]
     nq = args.nq or w["nq"]
     k, width, max_iters, degree = w["k"], w["width"], w["max_iters"], w["degree"]
+    sha = sources_sha()
 
     # ------------------------------------------------------------------ inputs (resident in HBM)
     t0 = time.time()
@@ -110,6 +163,17 @@ def main() -> int:
     else:
         inputs.knn_graph_clustered(part, d_in or degree, progress=(lambda c, t: log(f"graph: cluster {c}/{t}"),
                                                                    max(1, w["centres"] // 8)))
+
+    def event_ms(fn, reps):
+        """Mean duration of fn() by HIP events on the stream the library launches on (torch's current stream)."""
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+        for a, b in evs:
+            a.record()
+            fn()
+            b.record()
+        torch.cuda.synchronize()
+        return sum(a.elapsed_time(b) for a, b in evs) / reps
+
     opt = None
     if d_in:
         # the kNN lists are built d_in long; their first `degree` columns are the workload's kNN graph
@@ -118,31 +182,17 @@ def main() -> int:
         log(f"kNN lists of length {d_in} built in {time.time() - t0:.1f} s")
         ws = torch.empty(ann.ann_graph_optimize_workspace_bytes(w["n"], d_in, degree), dtype=torch.uint8, device=dev)
         opt_graph = torch.empty((w["n"], degree), dtype=torch.int32, device=dev)
-
-        def timed(fn):
-            fn()  # warm-up
-            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            a.record()
-            fn()
-            b.record()
-            torch.cuda.synchronize()
-            return a.elapsed_time(b)
-
-        prune_ms = timed(lambda: ann.ann_graph_prune(knn, degree, pruned=opt_graph))
-        build_ms = timed(lambda: ann.ann_graph_optimize(knn, degree, out_graph=opt_graph, workspace=ws))
+        ann.ann_graph_prune(knn, degree, pruned=opt_graph)  # warm-up
+        prune_ms = event_ms(lambda: ann.ann_graph_prune(knn, degree, pruned=opt_graph), 1)
+        ann.ann_graph_optimize(knn, degree, out_graph=opt_graph, workspace=ws)
+        build_ms = event_ms(lambda: ann.ann_graph_optimize(knn, degree, out_graph=opt_graph, workspace=ws), 1)
         del ws
         opt = {"from_degree": d_in, "degree": degree,
                "build_ms": {"graph_prune_kernel": round(prune_ms, 2), "reverse_edges_and_merge": round(build_ms - prune_ms, 2),
                             "ann_graph_optimize": round(build_ms, 2)}}
-        # d_in rows of d_in ids read per node, the node's own row, the pruned row written
-        prune_bytes = w["n"] * (d_in * d_in * 4 + d_in * 4 + degree * 4)
-        opt["roofline"] = {"bound": "hbm", "kernel": "graph_prune_kernel", "achieved": round(prune_bytes / prune_ms / 1e6, 1),
-                           "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(prune_bytes / prune_ms / 1e6 / HBM_PEAK_GBPS, 4),
-                           "traffic": read_traffic("graph_prune_kernel", args.workload), "kernel_ms": round(prune_ms, 2),
-                           "algorithmic_bytes_per_launch": prune_bytes,
-                           "note": "neighbours' rows are read once per listing node, mostly from L2 (see traffic)"}
         log(f"graph optimisation {d_in} -> {degree}: prune {prune_ms:.1f} ms, whole build {build_ms:.1f} ms")
-        if not args.no_oracle:
+        opt["build_roofline"] = prune_roofline(args.workload, sha, w["n"], d_in, degree, prune_ms)
+        if not args.no_oracle and not args.profile:
             from oracle import sampling
 
             t1 = time.time()
@@ -161,75 +211,82 @@ def main() -> int:
         queries = inputs.unit_mixture_queries(part, nq_max, seed=SEED + 1)
     torch.cuda.synchronize()
     log(f"index and {nq_max} queries generated in {time.time() - t0:.1f} s")
-    n_gt = min(2000, nq)
+
+    def load(graph):
+        return ann.ann_index_load(part.vectors, graph, metric=metric, n_entry=32, entry_mode=ann.ANN_ENTRY_ROUTED,
+                                  seed=SEED + 2, centroids=part.centres, cluster_offsets=part.offsets, route_c=1)
+
+    h = load(part.graph)
+    row_bytes = w["dim"] * part.vectors.element_size()
+    q = queries[:nq]
+    out_ids = torch.empty((nq, k), dtype=torch.int32, device=dev)
+    out_d = torch.empty((nq, k), dtype=torch.int32 if dt == "u8" else torch.float32, device=dev)
+
+    def search(handle, it, **kw):
+        return ann.ann_search(handle, q, k, it, width, max_iters, out_ids=out_ids, out_dists=out_d, **kw)
+
+    if args.profile:
+        return profile_pass(args, ann, torch, h, load(opt_graph) if opt is not None else None, q, search, sha)
+
+    # ------------------------------------------------------------------ smallest itopk with recall - 2 SE >= 0.95
+    n_gt = min(N_TRUTH, nq)
     t0 = time.time()
     truth = inputs.ground_truth(part, queries[:n_gt], k)
     torch.cuda.synchronize()
     log(f"exact ground truth for {n_gt} queries in {time.time() - t0:.1f} s")
 
-    h = ann.ann_index_load(part.vectors, part.graph, metric=metric, n_entry=32, entry_mode=ann.ANN_ENTRY_ROUTED,
-                           seed=SEED + 2, centroids=part.centres, cluster_offsets=part.offsets, route_c=1)
-    row_bytes = w["dim"] * part.vectors.element_size()
+    def recall_of(ids):
+        per_query = inputs.recall_per_query(ids, truth)
+        return float(per_query.mean()), float(per_query.std(unbiased=True) / per_query.numel() ** 0.5)
 
-    # ------------------------------------------------------------------ smallest itopk with recall >= 0.95
-    recall_by_itopk = {}
-    itopk = None
-    for cand in w["itopk_sweep"]:
-        ids, _ = ann.ann_search(h, queries[:n_gt], k, cand, width, max_iters)
-        torch.cuda.synchronize()
-        recall_by_itopk[cand] = round(inputs.recall(ids, truth), 4)
-        if recall_by_itopk[cand] >= 0.95:
-            itopk = cand
-            break
-    log(f"recall@{k} by itopk: {recall_by_itopk}")
+    def choose_itopk(handle, candidates, fixed):
+        table, chosen = {}, None
+        for cand in ([fixed] if fixed else candidates):
+            ids, _ = ann.ann_search(handle, queries[:n_gt], k, cand, width, max_iters)
+            torch.cuda.synchronize()
+            r, se = recall_of(ids)
+            table[cand] = [round(r, 4), round(se, 4)]
+            if r - 2 * se >= RECALL_TARGET:
+                chosen = cand
+                break
+        return table, chosen
+
+    recall_by_itopk, itopk = choose_itopk(h, w["itopk_sweep"], args.itopk)
+    log(f"recall@{k} [mean, standard error] by itopk: {recall_by_itopk}")
     target_met = itopk is not None
     if itopk is None:
-        itopk = w["itopk_sweep"][-1]
-
-    q = queries[:nq]
-    out_ids = torch.empty((nq, k), dtype=torch.int32, device=dev)
-    out_d = torch.empty((nq, k), dtype=torch.int32 if dt == "u8" else torch.float32, device=dev)
+        itopk = args.itopk or w["itopk_sweep"][-1]
 
     # ------------------------------------------------------------------ timed steps: whole hot path
     for _ in range(args.warmup):
-        ann.ann_search(h, q, k, itopk, width, max_iters, out_ids=out_ids, out_dists=out_d)
+        search(h, itopk)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        ann.ann_search(h, q, k, itopk, width, max_iters, out_ids=out_ids, out_dists=out_d)
+        search(h, itopk)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     ms_per_step = wall / args.steps * 1e3
     qps = nq / (wall / args.steps)
-    rec = inputs.recall(out_ids[:n_gt], truth)
-    log(f"{nq} queries/step, itopk {itopk}: {ms_per_step:.2f} ms/step, {qps:.3e} q/s, recall@{k} {rec:.4f}")
+    rec, rec_se = recall_of(out_ids[:n_gt])
+    log(f"{nq} queries/step, itopk {itopk}: {ms_per_step:.2f} ms/step, {qps:.3e} q/s, recall@{k} {rec:.4f} +- {rec_se:.4f}")
 
-    # ------------------------------------------------------------------ the two kernels on their own (HIP events on the launch stream)
-    def event_ms(fn, reps):
-        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
-        for a, b in evs:
-            a.record()
-            fn()
-            b.record()
-        torch.cuda.synchronize()
-        return sum(a.elapsed_time(b) for a, b in evs) / reps
-
+    # ------------------------------------------------------------------ the stages on their own (HIP events on the launch stream)
     routes = ann.ann_route(h, q)
     route_ms = event_ms(lambda: ann.ann_route(h, q, out_clusters=routes), args.steps)
-    search_ms = event_ms(lambda: ann.ann_search(h, q, k, itopk, width, max_iters, out_ids=out_ids, out_dists=out_d,
-                                                routes=routes), args.steps)
+    search_ms = event_ms(lambda: search(h, itopk, routes=routes), args.steps)
     # the same kernel without the cluster-grouped execution order: every gather goes to HBM
     ann.ann_index_set_option(h, ann.ANN_OPT_CLUSTER_ORDER_MIN_QUERIES, -1)
-    ungrouped_ms = event_ms(lambda: ann.ann_search(h, q, k, itopk, width, max_iters, out_ids=out_ids, out_dists=out_d,
-                                                   routes=routes), max(2, args.steps // 2))
+    search(h, itopk, routes=routes)
+    drawn_ms = event_ms(lambda: search(h, itopk, routes=routes), max(2, args.steps // 2))
     ann.ann_index_set_option(h, ann.ANN_OPT_CLUSTER_ORDER_MIN_QUERIES, 16384)
     counters = torch.zeros((nq, 4), dtype=torch.int32, device=dev)
-    ann.ann_search(h, q, k, itopk, width, max_iters, out_ids=out_ids, out_dists=out_d, counters=counters)
+    search(h, itopk, counters=counters)
     torch.cuda.synchronize()
     cm = counters.double().mean(0).tolist()
     actual_bq = metrics.algorithmic_bytes_per_query(cm[1], cm[2], row_bytes, degree, row_bytes, k)
-    log(f"kernels: route {route_ms:.3f} ms, beam search {search_ms:.3f} ms; per query: rounds {cm[0]:.1f}, rows "
-        f"gathered {cm[1]:.0f}, graph rows {cm[2]:.0f}, table resets {cm[3]:.2f}")
+    log(f"stages: route {route_ms:.3f} ms, order + beam search {search_ms:.3f} ms (drawn order {drawn_ms:.3f} ms); per query: "
+        f"rounds {cm[0]:.1f}, rows gathered {cm[1]:.0f}, graph rows {cm[2]:.0f}, table resets {cm[3]:.2f}")
 
     # ------------------------------------------------------------------ stage 1 of the next batch under stage 3 of this one
     # (two streams; the single-GPU shadow of the paper's two-microbatch pipeline, Sec. 3.2)
@@ -244,7 +301,7 @@ def main() -> int:
     for i in range(args.steps):
         cur, nxt = i % 2, (i + 1) % 2
         s_search.wait_event(routed[cur])
-        ann.ann_search(h, q, k, itopk, width, max_iters, out_ids=out_ids, out_dists=out_d, routes=bufs[cur], stream=s_search)
+        search(h, itopk, routes=bufs[cur], stream=s_search)
         searched[cur].record(s_search)
         if i >= 1:
             s_route.wait_event(searched[nxt])  # the search that read bufs[nxt] has finished
@@ -271,7 +328,7 @@ def main() -> int:
         sweep[str(b)] = round(b * reps / (time.perf_counter() - t0), 1)
     log(f"q/s by batch size: {sweep}")
     # leave the outputs of the full batch in place for the parity check
-    ann.ann_search(h, q, k, itopk, width, max_iters, out_ids=out_ids, out_dists=out_d)
+    search(h, itopk)
     torch.cuda.synchronize()
 
     # ------------------------------------------------------------------ CPU oracle: baseline, parity sample, algorithmic counters
@@ -323,33 +380,31 @@ def main() -> int:
 
     # ------------------------------------------------------------------ the same measurement on the optimized graph
     if opt is not None:
-        h2 = ann.ann_index_load(part.vectors, opt_graph, metric=metric, n_entry=32, entry_mode=ann.ANN_ENTRY_ROUTED,
-                                seed=SEED + 2, centroids=part.centres, cluster_offsets=part.offsets, route_c=1)
-        opt_recalls, opt_itopk = {}, None
-        for cand in w["opt_itopk_sweep"]:
-            ids, _ = ann.ann_search(h2, queries[:n_gt], k, cand, width, max_iters)
-            torch.cuda.synchronize()
-            opt_recalls[cand] = round(inputs.recall(ids, truth), 4)
-            if opt_recalls[cand] >= 0.95:
-                opt_itopk = cand
-                break
+        h2 = load(opt_graph)
+        opt_recalls, opt_itopk = choose_itopk(h2, w["opt_itopk_sweep"], args.opt_itopk)
         opt["recall_target_met"] = opt_itopk is not None
-        opt_itopk = opt_itopk or w["opt_itopk_sweep"][-1]
+        opt_itopk = opt_itopk or args.opt_itopk or w["opt_itopk_sweep"][-1]
         for _ in range(args.warmup):
-            ann.ann_search(h2, q, k, opt_itopk, width, max_iters, out_ids=out_ids, out_dists=out_d)
+            search(h2, opt_itopk)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for _ in range(args.steps):
-            ann.ann_search(h2, q, k, opt_itopk, width, max_iters, out_ids=out_ids, out_dists=out_d)
+            search(h2, opt_itopk)
         torch.cuda.synchronize()
         opt_wall = (time.perf_counter() - t0) / args.steps
-        ann.ann_search(h2, q, k, opt_itopk, width, max_iters, out_ids=out_ids, out_dists=out_d, counters=counters)
+        opt_routes = ann.ann_route(h2, q)
+        opt_search_ms = event_ms(lambda: search(h2, opt_itopk, routes=opt_routes), args.steps)
+        search(h2, opt_itopk, counters=counters)
         torch.cuda.synchronize()
         ocm = counters.double().mean(0).tolist()
-        opt.update({"itopk": opt_itopk, "recall_by_itopk": opt_recalls, "recall_at_k": round(inputs.recall(out_ids[:n_gt], truth), 4),
+        orec, orec_se = recall_of(out_ids[:n_gt])
+        opt.update({"itopk": opt_itopk, "recall_by_itopk": opt_recalls, "recall_at_k": round(orec, 4), "recall_se": round(orec_se, 4),
                     "qps": round(nq / opt_wall, 1), "ms_per_step": round(opt_wall * 1e3, 3),
                     "per_query": {"rounds": round(ocm[0], 2), "rows_gathered": round(ocm[1], 1), "graph_rows": round(ocm[2], 1)}})
-        log(f"optimized graph: itopk {opt_itopk}, recall {opt['recall_at_k']}, {opt['qps']:.3e} q/s, rounds {ocm[0]:.1f}")
+        gathered = metrics.algorithmic_bytes_per_query(ocm[1], ocm[2], row_bytes, degree, row_bytes, k) * nq
+        opt["roofline"] = search_roofline(read_profile("beam_search_kernel", args.workload), "optimized", sha, nq, opt_search_ms,
+                                          gathered, None, None, opt_itopk)
+        log(f"optimized graph: itopk {opt_itopk}, recall {orec:.4f}, {opt['qps']:.3e} q/s, rounds {ocm[0]:.1f}")
         ann.ann_free(h2)
 
     # ------------------------------------------------------------------ what random whole-row reads reach on this table
@@ -364,39 +419,19 @@ def main() -> int:
     ann.ann_free(hg)
     del rnd
 
-    # a plain copy of known size (1 GiB read, 1 GiB written): calibrates profiler byte counters
-    src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).random_(0, 256)
-    dst = torch.empty_like(src)
-    for _ in range(3):
-        ann.ann_calibration_copy(dst, src)
-    torch.cuda.synchronize()
-    del src, dst
-
     # ------------------------------------------------------------------ roofline of the dominant kernel
+    algo_bytes = None
     if algo["n_dist"] is not None:
-        algo_bq = metrics.algorithmic_bytes_per_query(algo["n_dist"], algo["n_parents"], row_bytes, degree, row_bytes, k)
-    else:
-        algo_bq = None
-    traffic = read_traffic("beam_search_kernel", args.workload)
-    roofline = None
-    if algo_bq is not None:
-        achieved = algo_bq * nq / (search_ms * 1e-3) / 1e9
-        ungrouped = algo_bq * nq / (ungrouped_ms * 1e-3) / 1e9
-        roofline = {"bound": "hbm", "kernel": "beam_search_kernel", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
-                    "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
-                    "kernel_ms": round(search_ms, 3), "algorithmic_bytes_per_launch": round(algo_bq * nq),
-                    "note": "algorithmic bytes / kernel time; the batch runs grouped by cluster, so part of the rows "
-                            "comes from L2 and the figure can exceed what HBM alone delivers (see traffic); "
-                            "drawn_order is the same kernel with the grouping switched off, where traffic equals "
-                            "the algorithmic bytes",
-                    "drawn_order": {"kernel_ms": round(ungrouped_ms, 3), "achieved": round(ungrouped, 1),
-                                    "frac": round(ungrouped / HBM_PEAK_GBPS, 4),
-                                    "vs_random_row_gather": round(ungrouped / gather_gbps, 4)},
-                    "random_row_gather": {"achieved": round(gather_gbps, 1), "unit": "GB/s", "rows": n_rows,
-                                          "note": "ann_calibration_gather: a plain kernel that reads uniformly random "
-                                                  "whole rows of the same vector table and nothing else (non-temporal, "
-                                                  "eight loads in flight per lane): what this access pattern gets "
-                                                  "without any search work, a reference rather than a hard limit"}}
+        algo_bytes = metrics.algorithmic_bytes_per_query(algo["n_dist"], algo["n_parents"], row_bytes, degree, row_bytes, k) * nq
+    roofline = search_roofline(read_profile("beam_search_kernel", args.workload), "grouped", sha, nq, search_ms,
+                               actual_bq * nq, algo_bytes, drawn_ms, itopk)
+    roofline["random_row_gather"] = {
+        "achieved": round(gather_gbps, 1), "unit": "GB/s", "rows": n_rows,
+        "note": "ann_calibration_gather: a plain kernel that reads uniformly random whole rows of the same vector table "
+                "and nothing else (non-temporal, eight loads in flight per lane): what this access pattern gets without "
+                "any search work, a reference rather than a hard limit"}
+    if roofline.get("drawn_order"):
+        roofline["drawn_order"]["vs_random_row_gather"] = round(roofline["drawn_order"]["achieved"] / gather_gbps, 4)
 
     line = {
         "metric": f"queries/sec at recall@{k}>=0.95 on 1 MI355X", "value": round(qps, 1), "unit": "queries/s",
@@ -405,29 +440,118 @@ def main() -> int:
         "config": {"workload": f"{args.workload}: {w['text']}; {nq} queries per step in drawn order, k={k}, "
                                f"itopk={itopk}, width={width}, max_iters={max_iters}, 32 routed entries (route_c=1)",
                    "itopk": itopk, "queries_per_step": nq},
-        "recall_at_k": round(rec, 4), "k": k, "recall_target_met": target_met, "recall_by_itopk": recall_by_itopk,
-        "bytes_per_query": {"algorithmic": None if algo_bq is None else round(algo_bq), "gathered": round(actual_bq)},
+        "recall_at_k": round(rec, 4), "recall_se": round(rec_se, 4), "recall_queries": n_gt, "k": k,
+        "recall_rule": f"smallest itopk of the sweep whose recall - 2 standard errors >= {RECALL_TARGET}",
+        "recall_target_met": target_met, "recall_by_itopk": recall_by_itopk,
+        "bytes_per_query": {"algorithmic": None if algo_bytes is None else round(algo_bytes / nq), "gathered": round(actual_bq)},
         "per_query": {"rounds": round(cm[0], 2), "rows_gathered": round(cm[1], 1), "graph_rows": round(cm[2], 1),
                       "rows_scored_by_oracle": algo["n_dist"]},
-        "kernel_ms": {"route_kernel": round(route_ms, 3), "beam_search_kernel": round(search_ms, 3)},
+        "stage_ms": {"route": round(route_ms, 3), "order_and_beam_search": round(search_ms, 3)},
         "qps_two_streams": round(overlapped_qps, 1), "qps_by_batch": sweep, "parity": parity, "optimized_graph": opt,
-        "roofline": roofline, "cpu_baseline": cpu_baseline,
+        "sources_sha": sha, "roofline": roofline, "cpu_baseline": cpu_baseline,
     }
     print(json.dumps(line), flush=True)
     return 0
 
 
-def read_traffic(kernel: str, workload: str):
-    """HBM bytes per launch of `kernel`, from the committed rocprofv3 --pmc summary of this
-    workload (profiles/), or None if none has been recorded."""
-    path = os.path.join(ROOT, "profiles", f"{kernel}_{workload}_pmc.txt")
-    try:
-        for ln in open(path):
-            if ln.startswith("traffic_bytes_per_launch"):
-                return float(ln.split("=")[1])
-    except OSError:
-        pass
-    return None
+def search_roofline(prof: dict, leg: str, sha: str, nq: int, kernel_ms: float, gathered_bytes: float, algo_bytes,
+                    drawn_ms, itopk: int) -> dict:
+    """Roofline object of one timed configuration of beam_search_kernel ("grouped" or "optimized").
+
+    prof: the committed counter summary; its figures are per launch of `nq_profiled` queries at `itopk_profiled`
+    and are used only if they were taken on these sources, this batch size and this list size."""
+    fresh = bool(prof) and prof.get("sources_sha") == sha and prof.get(f"{leg}.nq") == nq and prof.get(f"{leg}.itopk") == itopk
+    sec = kernel_ms * 1e-3
+    counters = {"file": "profiles/beam_search_kernel_*_pmc.txt", "fresh": fresh,
+                "why": None if fresh else ("no counters recorded" if not prof else
+                                           "recorded on other kernel sources, batch or list size: not used")}
+    hbm_view = {"traffic": None, "achieved": None, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": None, "dram_read_bytes": None,
+                "gathered_bytes_per_launch": round(gathered_bytes),
+                "note": "measured bytes between L2 and the fabric (FETCH_SIZE + WRITE_SIZE, scaled by the same counters on a "
+                        "copy of known size) / kernel time; bytes the kernel gathers beyond this were L2 hits"}
+    drawn = None
+    if drawn_ms is not None and algo_bytes is not None:
+        gbps = algo_bytes / (drawn_ms * 1e-3) / 1e9
+        drawn = {"bound": "hbm", "kernel_ms": round(drawn_ms, 3), "achieved": round(gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                 "frac": round(gbps / HBM_PEAK_GBPS, 4), "algorithmic_bytes_per_launch": round(algo_bytes),
+                 "traffic": prof.get("drawn.traffic_bytes") if fresh else None,
+                 "note": "the same kernel with the cluster grouping switched off: every gather goes to HBM and the measured "
+                         "traffic equals the algorithmic bytes; this is the figure to hold against the HBM roofline"}
+    if fresh:
+        traffic = prof[f"{leg}.traffic_bytes"]
+        hbm_view.update({"traffic": traffic, "achieved": round(traffic / sec / 1e9, 1), "frac": round(traffic / sec / 1e9 / HBM_PEAK_GBPS, 4),
+                         "dram_read_bytes": prof.get(f"{leg}.dram_read_bytes")})
+        valu = prof[f"{leg}.valu_insts"]  # wavefront instructions per launch
+        tops = valu * 64 / sec / 1e12
+        out = {"bound": "alu", "kernel": "beam_search_kernel", "achieved": round(tops, 2), "peak": round(VALU_PEAK_TOPS, 2),
+               "unit": "TOP/s", "frac": round(tops / VALU_PEAK_TOPS, 4), "traffic": traffic, "kernel_ms": round(kernel_ms, 3),
+               "valu_insts_per_query": round(valu / nq, 1), "valu_busy_frac_by_counter": prof.get(f"{leg}.valu_busy_frac"),
+               "note": "vector-ALU issue: vector instructions the launch issued (rocprofv3 SQ_INSTS_VALU) x 64 lanes / kernel "
+                       "time, against 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz; the launch is bound by instruction issue, "
+                       "not by bytes (see hbm)"}
+    elif drawn is not None:
+        out = dict(drawn, kernel="beam_search_kernel",
+                   note="no current instruction counters for the grouped launch: this is the drawn-order launch of the same "
+                        "kernel, which is bound by HBM (algorithmic bytes / kernel time)")
+    else:
+        out = {"bound": "hbm", "kernel": "beam_search_kernel", "achieved": None, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": None,
+               "traffic": None, "kernel_ms": round(kernel_ms, 3), "note": "no counters and no oracle run: nothing to hold against a roofline"}
+    out["counters"] = counters
+    out["hbm"] = hbm_view
+    if leg == "grouped":
+        out["drawn_order"] = drawn
+        out["algorithmic_bytes_per_launch"] = None if algo_bytes is None else round(algo_bytes)
+    return out
+
+
+def prune_roofline(workload: str, sha: str, n: int, d_in: int, degree: int, prune_ms: float) -> dict:
+    prof = read_profile("graph_prune_kernel", workload)
+    fresh = bool(prof) and prof.get("sources_sha") == sha
+    algo = n * (d_in * d_in * 4 + d_in * 4 + degree * 4)  # d_in rows of d_in ids read per node, its own row, the pruned row
+    out = {"kernel": "graph_prune_kernel", "kernel_ms": round(prune_ms, 2), "algorithmic_bytes_per_launch": algo,
+           "counters": {"file": "profiles/graph_prune_kernel_*_pmc.txt", "fresh": fresh}}
+    if fresh:
+        valu, traffic = prof["prune.valu_insts"], prof["prune.traffic_bytes"]
+        tops = valu * 64 / (prune_ms * 1e-3) / 1e12
+        out.update({"bound": "alu", "achieved": round(tops, 2), "peak": round(VALU_PEAK_TOPS, 2), "unit": "TOP/s",
+                    "frac": round(tops / VALU_PEAK_TOPS, 4), "traffic": traffic,
+                    "hbm": {"traffic": traffic, "achieved": round(traffic / prune_ms / 1e6, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                            "frac": round(traffic / prune_ms / 1e6 / HBM_PEAK_GBPS, 4)},
+                    "note": "neighbours' rows are re-read from L2 (XCD-local walk), so the launch is bound by instruction "
+                            "issue and LDS, not by its algorithmic bytes"})
+    else:
+        out.update({"bound": "alu", "achieved": None, "peak": round(VALU_PEAK_TOPS, 2), "unit": "TOP/s", "frac": None, "traffic": None})
+    return out
+
+
+def profile_pass(args, ann, torch, h, h_opt, q, search, sha) -> int:
+    """The launches the rocprofv3 commands under profiles/ are for, in a fixed order, then their legend."""
+    w = WORKLOADS[args.workload]
+    itopk = args.itopk or w["itopk_sweep"][0]
+    sequence = []
+    for _ in range(1 + max(1, args.steps)):
+        search(h, itopk)
+        sequence.append("grouped")
+    ann.ann_index_set_option(h, ann.ANN_OPT_CLUSTER_ORDER_MIN_QUERIES, -1)
+    for _ in range(2):
+        search(h, itopk)
+        sequence.append("drawn")
+    if h_opt is not None:
+        for _ in range(1 + max(1, args.steps)):
+            search(h_opt, args.opt_itopk or w["opt_itopk_sweep"][0])
+            sequence.append("optimized")
+    src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0").random_(0, 256)
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        ann.ann_calibration_copy(dst, src)  # 1 GiB read, 1 GiB written: calibrates the byte counters
+    torch.cuda.synchronize()
+    print(json.dumps({"profile_pass": args.workload, "sources_sha": sha, "queries_per_launch": q.shape[0], "itopk": itopk,
+                      "opt_itopk": args.opt_itopk or (w.get("opt_itopk_sweep") or [0])[0],
+                      "beam_search_kernel_launches_of_full_batch": sequence,
+                      "graph_prune_kernel_launches": ["ann_graph_prune (warm-up)", "ann_graph_prune", "ann_graph_optimize (warm-up)",
+                                                      "ann_graph_optimize"] if h_opt is not None else [],
+                      "calibration_copy_bytes": 1 << 30}), flush=True)
+    return 0
 
 
 if __name__ == "__main__":

@@ -42,6 +42,7 @@ def _load():
         build(force=False)
         lib = ctypes.CDLL(_LIB)
         lib.oracle_search.restype = ctypes.c_int
+        lib.oracle_search_routed.restype = ctypes.c_int
         lib.oracle_bruteforce.restype = ctypes.c_int
         lib.oracle_entries.restype = ctypes.c_int
         lib.oracle_route.restype = ctypes.c_int
@@ -98,17 +99,24 @@ class Index:
                 ctypes.c_int32(self.n_clusters), ctypes.c_int32(self.route_c))
 
 
-def search(index: Index, queries, k, itopk, width, max_iters, forget_visited=False, n_threads=0):
-    """Returns (ids[nq,k] int32, dists[nq,k] int32|float32, counters dict of int64[nq])."""
+def search(index: Index, queries, k, itopk, width, max_iters, forget_visited=False, n_threads=0, routes=None):
+    """Returns (ids[nq,k] int32, dists[nq,k] int32|float32, counters dict of int64[nq]).
+
+    routes (int32 [nq, route_c], routed entry mode only): cluster ids used instead of the oracle's own
+    routing step; an id outside [0, n_clusters) names no cluster."""
     q = _c(queries)
     assert q.dtype == index.vectors.dtype and q.ndim == 2 and q.shape[1] == index.dim
     nq = q.shape[0]
     ids = np.empty((nq, k), np.int32)
     dists = np.empty((nq, k), np.int32 if index.dtype == DT_U8 else np.float32)
     iters, ndist, npar = (np.zeros(nq, np.int64) for _ in range(3))
-    rc = _load().oracle_search(*index._head(), _p(q), ctypes.c_int64(nq), ctypes.c_int32(k), ctypes.c_int32(itopk),
-                               ctypes.c_int32(width), ctypes.c_int32(max_iters), ctypes.c_int32(int(forget_visited)),
-                               _p(ids), _p(dists), _p(iters), _p(ndist), _p(npar), ctypes.c_int32(n_threads))
+    r = None
+    if routes is not None:
+        r = _c(routes, np.int32)
+        assert index.entry_mode == 1 and r.shape == (nq, index.route_c)
+    rc = _load().oracle_search_routed(*index._head(), _p(q), ctypes.c_int64(nq), ctypes.c_int32(k), ctypes.c_int32(itopk),
+                                      ctypes.c_int32(width), ctypes.c_int32(max_iters), ctypes.c_int32(int(forget_visited)),
+                                      _p(ids), _p(dists), _p(iters), _p(ndist), _p(npar), ctypes.c_int32(n_threads), _p(r))
     if rc != 0:
         raise ValueError("oracle_search rejected its arguments")
     return ids, dists, {"iters": iters, "n_dist": ndist, "n_parents": npar}

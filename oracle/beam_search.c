@@ -120,6 +120,8 @@ typedef struct {
     const void* centroids; /* n_clusters x dim, same dtype as the vectors, dense rows */
     const int64_t* cluster_offsets; /* n_clusters + 1; cluster c owns ids [off[c], off[c+1]) */
     int32_t n_clusters, route_c;
+    const int32_t* given_routes; /* NULL, or nq x route_c cluster ids that replace the routing step (stage 1
+                                    done elsewhere; an id outside [0, n_clusters) names no cluster) */
 } index_t;
 
 static size_t elem_size(int32_t dtype) { return dtype == DT_U8 ? 1 : dtype == DT_F16 ? 2 : 4; }
@@ -155,7 +157,10 @@ static int32_t entries_of(const index_t* ix, const void* q, int64_t qi, int32_t*
     int32_t* near = NULL;
     if (ix->entry_mode == 1) {
         near = (int32_t*)malloc(sizeof(int32_t) * (size_t)ix->route_c);
-        nearest_clusters(ix, q, near);
+        if (ix->given_routes)
+            memcpy(near, ix->given_routes + qi * ix->route_c, sizeof(int32_t) * (size_t)ix->route_c);
+        else
+            nearest_clusters(ix, q, near);
     }
     for (int32_t j = 0; j < ix->n_entry; ++j) {
         uint64_t z = mix64(ix->seed, (uint64_t)qi * (uint64_t)ix->n_entry + (uint64_t)j);
@@ -163,6 +168,7 @@ static int32_t entries_of(const index_t* ix, const void* q, int64_t qi, int32_t*
             out[cnt++] = (int32_t)(z % (uint64_t)ix->n);
         } else {
             int32_t c = near[j % ix->route_c];
+            if (c < 0 || c >= ix->n_clusters) continue; /* only a given route can be such: no cluster, no entry */
             int64_t lo = ix->cluster_offsets[c], hi = ix->cluster_offsets[c + 1];
             if (hi > lo) out[cnt++] = (int32_t)(lo + (int64_t)(z % (uint64_t)(hi - lo)));
         }
@@ -301,6 +307,7 @@ static index_t make_index(const void* vectors, int64_t n, int32_t dim, int32_t d
     ix.cluster_offsets = cluster_offsets;
     ix.n_clusters = n_clusters;
     ix.route_c = route_c;
+    ix.given_routes = NULL;
     return ix;
 }
 
@@ -309,20 +316,24 @@ static index_t make_index(const void* vectors, int64_t n, int32_t dim, int32_t d
  * out_ids: nq*k int32.  out_dists: nq*k int32 (uint8 data) or float.
  * counters (each nq int64, may be NULL): expansion rounds, keys computed, graph
  * rows read.  forget_visited != 0 selects the forgetful visited set of the test
- * switch above.  Returns 0, or -1 on arguments it cannot serve.
+ * switch above.  routes (routed entry mode only, may be NULL): nq*route_c cluster ids that
+ * are used instead of the routing step, as when stage 1 ran elsewhere (paper Sec. 3.1: the
+ * classifier and the search are separate stages).  Returns 0, or -1 on arguments it cannot serve.
  */
-int oracle_search(const void* vectors, int64_t n, int32_t dim, int32_t dtype, int64_t row_stride_bytes,
+int oracle_search_routed(const void* vectors, int64_t n, int32_t dim, int32_t dtype, int64_t row_stride_bytes,
                   const int32_t* graph, int32_t degree, int32_t metric, int32_t n_entry, int32_t entry_mode,
                   uint64_t seed, const void* centroids, const int64_t* cluster_offsets, int32_t n_clusters,
                   int32_t route_c, const void* queries, int64_t nq, int32_t k, int32_t itopk, int32_t width,
                   int32_t max_iters, int32_t forget_visited, int32_t* out_ids, void* out_dists,
-                  int64_t* out_iters, int64_t* out_n_dist, int64_t* out_n_parents, int32_t n_threads) {
+                  int64_t* out_iters, int64_t* out_n_dist, int64_t* out_n_parents, int32_t n_threads,
+                  const int32_t* routes) {
     if (n < 1 || dim < 1 || degree < 1 || n_entry < 1 || k < 1 || itopk < k || width < 1 || max_iters < 0 ||
         nq < 0)
         return -1;
     if (entry_mode == 1 && (n_clusters < 1 || route_c < 1 || route_c > n_clusters)) return -1;
     index_t ix = make_index(vectors, n, dim, dtype, row_stride_bytes, graph, degree, metric, n_entry, entry_mode,
                             seed, centroids, cluster_offsets, n_clusters, route_c);
+    ix.given_routes = entry_mode == 1 ? routes : NULL;
     size_t qbytes = elem_size(dtype) * (size_t)dim;
     int64_t batch = (int64_t)width * degree;
     if (batch < n_entry) batch = n_entry;
@@ -362,6 +373,18 @@ int oracle_search(const void* vectors, int64_t n, int32_t dim, int32_t dtype, in
         free(scratch);
     }
     return failed ? -1 : 0;
+}
+
+/* The same with the routing step done by the oracle itself. */
+int oracle_search(const void* vectors, int64_t n, int32_t dim, int32_t dtype, int64_t row_stride_bytes,
+                  const int32_t* graph, int32_t degree, int32_t metric, int32_t n_entry, int32_t entry_mode,
+                  uint64_t seed, const void* centroids, const int64_t* cluster_offsets, int32_t n_clusters,
+                  int32_t route_c, const void* queries, int64_t nq, int32_t k, int32_t itopk, int32_t width,
+                  int32_t max_iters, int32_t forget_visited, int32_t* out_ids, void* out_dists,
+                  int64_t* out_iters, int64_t* out_n_dist, int64_t* out_n_parents, int32_t n_threads) {
+    return oracle_search_routed(vectors, n, dim, dtype, row_stride_bytes, graph, degree, metric, n_entry, entry_mode, seed,
+                                centroids, cluster_offsets, n_clusters, route_c, queries, nq, k, itopk, width, max_iters,
+                                forget_visited, out_ids, out_dists, out_iters, out_n_dist, out_n_parents, n_threads, NULL);
 }
 
 /* How many threads oracle_search will use when asked for n_threads (<=0: default). */

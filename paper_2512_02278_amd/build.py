@@ -77,5 +77,32 @@ def build(jobs: int = 8, extra_flags=()) -> str:
     return LIB
 
 
+CLANG = "/opt/rocm/llvm/bin/clang"
+SAN_FLAGS = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined", "-Xarch_host",
+             "-fno-sanitize-recover=undefined"]
+
+
+def build_host_sanitized() -> str:
+    """libann_san.so: the host code (ann_host.hip) under ASan + UBSan, linked with the kernel objects of the
+    last build().  For the host-only ABI checks; device code cannot be sanitised on this machine pool."""
+    objs = [o for o in sorted(glob.glob(os.path.join(OBJ, "*.hip.o"))) if not o.endswith("ann_host.hip.o")]
+    if not objs:
+        build()
+        objs = [o for o in sorted(glob.glob(os.path.join(OBJ, "*.hip.o"))) if not o.endswith("ann_host.hip.o")]
+    host = os.path.join(OBJ, "ann_host.san.o")
+    flags = [f for f in FLAGS if f != "-O3" and not f.startswith("-Rpass")]
+    r = subprocess.run(["hipcc", *flags, "-O1", "-g", *SAN_FLAGS, "-c", os.path.join(CSRC, "ann_host.hip"), "-o", host],
+                       capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError(f"hipcc (sanitized host pass) failed:\n{r.stderr}")
+    lib = os.path.join(OBJ, "libann_san.so")
+    subprocess.run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-fsanitize=address", "-fsanitize=undefined",
+                    "-fno-gpu-sanitize", "-o", lib, host, *objs], check=True)
+    return lib
+
+
 if __name__ == "__main__":
-    print(build(extra_flags=sys.argv[1:]))
+    if "--sanitize-host" in sys.argv[1:]:
+        print(build_host_sanitized())
+    else:
+        print(build(extra_flags=sys.argv[1:]))

@@ -238,8 +238,10 @@ def knn_graph_clustered(part: Partition, degree: int, n_near: int = 4, row_block
 
 
 def ground_truth(part: Partition, queries: torch.Tensor, k: int, col_block: int = 1 << 20,
-                 row_block: int = 2048) -> torch.Tensor:
-    """Exact top-k ids [nq, k] int32 over the whole partition under (key, id)."""
+                 row_block: int = 1024) -> torch.Tensor:
+    """Exact top-k ids [nq, k] int32 over the whole partition under (key, id).
+
+    row_block * col_block stays below 2^31 elements (index arithmetic of the library's nonzero)."""
     x = part.vectors
     dev = x.device
     n = x.shape[0]
@@ -277,12 +279,20 @@ def ground_truth(part: Partition, queries: torch.Tensor, k: int, col_block: int 
     return out
 
 
-def recall(found: torch.Tensor, truth: torch.Tensor) -> float:
-    """Mean over queries of |found ∩ truth| / k (ids of -1 never match; a repeated id counts once)."""
+def recall_per_query(found: torch.Tensor, truth: torch.Tensor) -> torch.Tensor:
+    """|found ∩ truth| / k for every query, float64 [nq] (ids of -1 never match; a repeated id counts once)."""
     f = found.to(torch.int64)
     t = truth.to(torch.int64).to(f.device)
-    hit = ((t[:, :, None] == f[:, None, :]) & (t[:, :, None] >= 0)).any(2)
-    return float(hit.float().sum() / (truth.shape[0] * truth.shape[1]))
+    out = torch.empty(t.shape[0], dtype=torch.float64, device=f.device)
+    for lo in range(0, t.shape[0], 4096):
+        tt, ff = t[lo:lo + 4096], f[lo:lo + 4096]
+        out[lo:lo + 4096] = ((tt[:, :, None] == ff[:, None, :]) & (tt[:, :, None] >= 0)).any(2).double().sum(1) / t.shape[1]
+    return out
+
+
+def recall(found: torch.Tensor, truth: torch.Tensor) -> float:
+    """Mean over queries of |found ∩ truth| / k."""
+    return float(recall_per_query(found, truth).mean())
 
 
 def graph_stats(part: Partition) -> dict:

@@ -341,6 +341,95 @@ def test_routed_entries_fall_in_the_nearest_clusters(oracle, dt):
         assert (ent[i] >= 0).sum() == want
 
 
+def _splitmix64_stream(seed, count):
+    """The published splitmix64 generator, written out here on its own: state += golden-ratio
+    constant, output = the three-step xor-shift-multiply finaliser of the new state."""
+    m = (1 << 64) - 1
+    out, state = [], seed & m
+    for _ in range(count):
+        state = (state + 0x9E3779B97F4A7C15) & m
+        z = state
+        z = ((z ^ (z >> 30)) * 0xBF58476D1CE4E5B9) & m
+        z = ((z ^ (z >> 27)) * 0x94D049BB133111EB) & m
+        out.append(z ^ (z >> 31))
+    return out
+
+
+def test_routed_entry_ids_follow_the_slot_rule_and_the_generator(oracle):
+    """Entry j of the query at batch position i takes output number i*n_entry + j of the splitmix64
+    stream started at the seed, goes to the (j mod route_c)-th nearest cluster c, and is
+    off[c] + z mod |c|; an empty cluster gives no entry for its slots."""
+    rng = np.random.default_rng(31)
+    n_clusters, dim, n_entry, route_c, seed, nq = 9, 8, 7, 3, 0xDEADBEEFCAFE, 11
+    cen = random_vectors(rng, n_clusters, dim, "f32")
+    sizes = rng.integers(1, 40, n_clusters)
+    sizes[[2, 5]] = 0
+    off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+    n = int(off[-1])
+    x = random_vectors(rng, n, dim, "f32")
+    q = random_vectors(rng, nq, dim, "f32")
+    ix = oracle.Index(x, np.zeros((n, 1), np.int32), n_entry=n_entry, entry_mode=1, seed=seed, centroids=cen,
+                      cluster_offsets=off, route_c=route_c)
+    ent = oracle.entries(ix, q)
+    z = _splitmix64_stream(seed, nq * n_entry)
+    saw_empty = False
+    for i in range(nq):
+        keys = np_keys(q[i], cen, 0)
+        near = np.lexsort((np.arange(n_clusters), keys))[:route_c]
+        want = []
+        for j in range(n_entry):
+            c = int(near[j % route_c])
+            if sizes[c] == 0:
+                saw_empty = True
+                continue
+            want.append(int(off[c]) + z[i * n_entry + j] % int(sizes[c]))
+        got = [int(e) for e in ent[i] if e >= 0]
+        assert got == want, (i, got, want)
+    assert saw_empty
+    # uniform mode, same stream: z mod n
+    ix0 = oracle.Index(x, np.zeros((n, 1), np.int32), n_entry=n_entry, entry_mode=0, seed=seed)
+    ent0 = oracle.entries(ix0, q)
+    assert ent0.tolist() == [[z[i * n_entry + j] % n for j in range(n_entry)] for i in range(nq)]
+
+
+def test_given_routes_replace_the_routing_step(oracle):
+    """Searching with the oracle's own routes handed in gives the oracle's own answer; a route id
+    outside the clusters names no cluster (no entries from it; padding if a query has no other)."""
+    rng = np.random.default_rng(32)
+    x, g, q = _clustered_case(rng, "u8")
+    n = len(x)
+    off = np.array([0, n // 3, n // 3, n], np.int64)  # cluster 1 is empty
+    cen = np.stack([x[: n // 3].mean(0), x[0] * 0, x[n // 3:].mean(0)]).astype(np.uint8)
+    ix = oracle.Index(x, g, n_entry=8, entry_mode=1, seed=3, centroids=cen, cluster_offsets=off, route_c=2)
+    a = oracle.search(ix, q, 5, 16, 2, 30)
+    r = oracle.route(cen, q, 2, 0)
+    b = oracle.search(ix, q, 5, 16, 2, 30, routes=r)
+    assert all(np.array_equal(u, v) for u, v in zip(a[:2], b[:2]))
+    bad = r.copy()
+    bad[0] = [-1, 3]
+    bad[1, 1] = 7
+    c = oracle.search(ix, q, 5, 16, 2, 30, routes=bad)
+    assert (c[0][0] == -1).all() and (c[1][0] == np.iinfo(np.int32).max).all() and c[2]["n_dist"][0] == 0
+    ix1 = oracle.Index(x, g, n_entry=8, entry_mode=1, seed=3, centroids=cen, cluster_offsets=off, route_c=2)
+    ent = oracle.entries(ix1, q[1:2])  # query 0 of that call: other stream positions, so compare through the search only
+    assert np.array_equal(c[0][2:], a[0][2:]) and np.array_equal(c[1][2:], a[1][2:])
+    assert ent.shape == (1, 8)
+
+
+def test_half_precision_decoding_on_explicit_bit_patterns(oracle):
+    """fp16 inputs are decoded by the format's definition; checked against numpy's float16 on
+    zeros, the smallest and largest subnormals, the smallest normal, 1, the largest finite value
+    and both infinities, through key = -q*x with q = 1."""
+    bits = np.array([0x0000, 0x8000, 0x0001, 0x8001, 0x03FF, 0x83FF, 0x0200, 0x0400, 0x8400, 0x3C00, 0xBC00, 0x3555,
+                     0x7BFF, 0xFBFF, 0x7C00, 0xFC00], np.uint16)
+    x = bits.view(np.float16).reshape(-1, 1)
+    q = np.ones((1, 1), np.float16)
+    got = oracle.keys(x, q, np.arange(len(bits), dtype=np.int32)[None, :], metric=1)[0]
+    want = -x[:, 0].astype(np.float64)
+    assert np.array_equal(got, want)
+    assert got[2] == -2.0 ** -24 and got[4] == -(1023 * 2.0 ** -24) and got[12] == -65504.0 and np.isneginf(got[14])
+
+
 # ----------------------------------------------------------------------------- P7 the paper's worked example
 def _golden():
     vals = {}
