@@ -1,9 +1,11 @@
 // Beam search kernel: one wavefront (64 lanes) per query.
 //
 // State of a query:
-//   * candidate list: 64*LPL packed keys in registers, ascending, blocked layout
-//     (wave.h).  A packed key is (ordered key << 32) | (id << 1) | expanded, so one
-//     unsigned 64-bit compare orders by (key, id) and the expanded mark rides along.
+//   * candidate list: 64*LPL packed keys in registers, ascending, striped layout
+//     (wave.h: entry e in register e / 64, lane e % 64; LPL is any of 1..8, so a list
+//     of 129..192 entries costs three registers per lane, not four).  A packed key is
+//     (ordered key << 32) | (id << 1) | expanded, so one unsigned 64-bit compare
+//     orders by (key, id) and the expanded mark rides along.
 //   * visited set in LDS, two parts.  (a) An exact bitmap over the id ranges of
 //     the clusters the query was routed to ("windows"): a K-means partition is
 //     stored as contiguous ids, and nearly every node a query scores lies in its
@@ -180,13 +182,17 @@ struct BeamSearch {
     // (the empty key while the list is not full).
     __device__ __forceinline__ uint64_t list_worst() const {
         const int e = p.itopk - 1;
-        uint64_t mine = kInfKey;
+        // lane e % 64 of every register is read and the register chosen among the scalars: choosing the
+        // register first would index the list by a run-time value and push the whole search state into
+        // scratch memory
+        uint64_t w = kInfKey;
 #pragma unroll
-        for (int r = 0; r < LPL; ++r)
-            if (lane * LPL + r == e) mine = L[r];
-        const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)mine, e / LPL);
-        const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(mine >> 32), e / LPL);
-        return ((uint64_t)hi << 32) | lo;
+        for (int r = 0; r < LPL; ++r) {
+            const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)L[r], e & 63);
+            const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(L[r] >> 32), e & 63);
+            if ((e >> 6) == r) w = ((uint64_t)hi << 32) | lo;
+        }
+        return w;
     }
 
     // Gathers rows cid[0..m) and writes the packed keys that can enter the list to
@@ -250,17 +256,19 @@ struct BeamSearch {
 #pragma unroll
         for (int r = 0; r < R; ++r) ckey[base + lane * R + r] = c[r];
         lds_sync();
-        // smallest 64*LPL of (list, sorted batch): element e against batch element 64*LPL-1-e
-#pragma unroll
-        for (int r = 0; r < LPL; ++r) {
-            const int j = 64 * LPL - 1 - (lane * LPL + r);
-            const uint64_t o = j < 64 * R ? ckey[base + j] : kInfKey;
-            L[r] = o < L[r] ? o : L[r];
-        }
-        bitonic_merge<LPL>(L, lane);
+        // smallest 64*LPL of (list, sorted batch): list entry e against batch element 64*LPL-1-e, which
+        // leaves one run that rises and then falls.  Register r holds entries 64r .. 64r+63, so whole
+        // registers either have a partner in the batch or not.
 #pragma unroll
         for (int r = 0; r < LPL; ++r)
-            if (lane * LPL + r >= p.itopk) L[r] = kInfKey;
+            if (LPL - r <= R) {  // known at compile time
+                const uint64_t o = ckey[base + 64 * LPL - 1 - (r * 64 + lane)];
+                L[r] = o < L[r] ? o : L[r];
+            }
+        striped_merge<LPL>(L, lane);
+#pragma unroll
+        for (int r = 0; r < LPL; ++r)
+            if (r * 64 + lane >= p.itopk) L[r] = kInfKey;
         lds_sync();
     }
 
@@ -290,18 +298,18 @@ struct BeamSearch {
             pos = lane == j ? below : pos;
         }
         // Every key goes to its place without a test: a place may lie up to s <= kInsertMax entries beyond
-        // the copy (entries pushed off the end), which is still inside this round's scratch or, for the
-        // (4, 2) list variant, in the first words of `parents`, dead until the next round rewrites them.
+        // the copy (entries pushed off the end), which is still inside this round's scratch or in the
+        // first words of `parents` (32 keys wide), dead until the next round rewrites them.
         // Whatever landed at or beyond itopk is then overwritten with the empty key.
-        static_assert(kInsertMax <= 8, "trash slots beyond the list copy");
+        static_assert(kInsertMax <= 32, "trash slots beyond the list copy");
 #pragma unroll
-        for (int r = 0; r < LPL; ++r) lcopy[lane * LPL + r + cnt[r]] = L[r];
+        for (int r = 0; r < LPL; ++r) lcopy[r * 64 + lane + cnt[r]] = L[r];
         if (lane < s) lcopy[pos + rank] = mine;
         lds_sync();
         for (int i = p.itopk + lane; i < 64 * LPL; i += 64) lcopy[i] = kInfKey;
         lds_sync();
 #pragma unroll
-        for (int r = 0; r < LPL; ++r) L[r] = lcopy[lane * LPL + r];
+        for (int r = 0; r < LPL; ++r) L[r] = lcopy[r * 64 + lane];
         worst = lcopy[p.itopk - 1];  // one broadcast read of the sorted copy
         lds_sync();
     }
@@ -382,28 +390,25 @@ struct BeamSearch {
         const int limit = (3 << p.hash_bits) >> 2;
         int iters = 0;
         for (; iters < p.max_iters; ++iters) {
-            // parents: the first <= width unexpanded entries in list order
-            int before = 0, total = 0;
-            bool un[LPL];
-            uint32_t ex[LPL];  // the entries' expanded flags
+            // parents: the first <= width unexpanded entries in list order.  Register r holds entries
+            // 64r .. 64r+63, so the registers are walked in order and the walk stops once `width` are found.
+            int total = 0;
 #pragma unroll
             for (int r = 0; r < LPL; ++r) {
-                // taken in the 32-bit low word (the compiler otherwise widens the test to the whole key)
-                asm("v_and_b32 %0, 1, %1" : "=v"(ex[r]) : "v"((uint32_t)L[r]));
-                un[r] = ex[r] == 0;
-                const uint64_t b = __ballot(un[r]);
-                before = rank_below(b, before);
-                total += __builtin_popcountll(b);
+                if (total < p.width) {  // uniform
+                    uint32_t ex;  // taken in the 32-bit low word (the compiler otherwise widens the test to the whole key)
+                    asm("v_and_b32 %0, 1, %1" : "=v"(ex) : "v"((uint32_t)L[r]));
+                    const bool un = ex == 0;
+                    const uint64_t b = __ballot(un);
+                    const int rank = rank_below(b, total);
+                    const bool take = un && rank < p.width;
+                    if (take) parents[rank] = (uint32_t)L[r] >> 1;
+                    L[r] |= (uint64_t)(take ? 1u : 0u);
+                    total += __builtin_popcountll(b);
+                }
             }
             if (total == 0) break;
             const int np = total < p.width ? total : p.width;
-#pragma unroll
-            for (int r = 0; r < LPL; ++r) {
-                const bool take = un[r] && before < np;
-                if (take) parents[before] = (uint32_t)L[r] >> 1;
-                L[r] |= (uint64_t)(take ? 1u : 0u);
-                before += (int)(ex[r] ^ 1u);
-            }
             n_parents += np;
             if (n_table + np * p.degree > limit) reset_table();
             lds_sync();
@@ -433,7 +438,7 @@ struct BeamSearch {
         // first k list entries
 #pragma unroll
         for (int r = 0; r < LPL; ++r) {
-            const int e = lane * LPL + r;
+            const int e = r * 64 + lane;
             if (e < p.k) {
                 const bool have = L[r] != kInfKey;
                 p.out_ids[qi * p.k + e] = have ? (int32_t)((uint32_t)L[r] >> 1) : -1;

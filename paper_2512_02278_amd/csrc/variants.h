@@ -20,8 +20,8 @@ namespace ann {
     X(kF32, kL2, 8, 3) X(kF32, kIP, 8, 3) X(kF32, kL2, 32, 4) X(kF32, kIP, 32, 4)
 
 // List variants (LPL, CPL); a request is served by the first one that is large enough.
-constexpr int kListVariants[][2] = {{1, 1}, {2, 2}, {4, 2}, {4, 4}, {4, 8}, {8, 8}};
-constexpr int kNumListVariants = 6;
+constexpr int kListVariants[][2] = {{1, 1}, {2, 2}, {3, 2}, {4, 2}, {4, 4}, {4, 8}, {8, 8}};
+constexpr int kNumListVariants = 7;
 
 template <int DT, int METRIC, int G, int NCH>
 hipError_t launch_search(const SearchParams& p, int list_variant, unsigned grid, size_t lds_bytes, hipStream_t stream);
@@ -37,10 +37,11 @@ hipError_t launch_route(const RouteParams& p, hipStream_t stream);
         switch (list_variant) {                                                                                 \
             case 0: hipLaunchKernelGGL((beam_search_kernel<Row, 1, 1>), dim3(grid), dim3(64), lds_bytes, stream, p); break; \
             case 1: hipLaunchKernelGGL((beam_search_kernel<Row, 2, 2>), dim3(grid), dim3(64), lds_bytes, stream, p); break; \
-            case 2: hipLaunchKernelGGL((beam_search_kernel<Row, 4, 2>), dim3(grid), dim3(64), lds_bytes, stream, p); break; \
-            case 3: hipLaunchKernelGGL((beam_search_kernel<Row, 4, 4>), dim3(grid), dim3(64), lds_bytes, stream, p); break; \
-            case 4: hipLaunchKernelGGL((beam_search_kernel<Row, 4, 8>), dim3(grid), dim3(64), lds_bytes, stream, p); break; \
-            case 5: hipLaunchKernelGGL((beam_search_kernel<Row, 8, 8>), dim3(grid), dim3(64), lds_bytes, stream, p); break; \
+            case 2: hipLaunchKernelGGL((beam_search_kernel<Row, 3, 2>), dim3(grid), dim3(64), lds_bytes, stream, p); break; \
+            case 3: hipLaunchKernelGGL((beam_search_kernel<Row, 4, 2>), dim3(grid), dim3(64), lds_bytes, stream, p); break; \
+            case 4: hipLaunchKernelGGL((beam_search_kernel<Row, 4, 4>), dim3(grid), dim3(64), lds_bytes, stream, p); break; \
+            case 5: hipLaunchKernelGGL((beam_search_kernel<Row, 4, 8>), dim3(grid), dim3(64), lds_bytes, stream, p); break; \
+            case 6: hipLaunchKernelGGL((beam_search_kernel<Row, 8, 8>), dim3(grid), dim3(64), lds_bytes, stream, p); break; \
             default: return hipErrorInvalidValue;                                                               \
         }                                                                                                       \
         return hipGetLastError();                                                                               \

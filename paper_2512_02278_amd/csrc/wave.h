@@ -1,9 +1,12 @@
 // Wavefront-level building blocks for gfx950 (wave64): lane exchange, group
 // reductions and bitonic networks over 64-bit keys held in registers.
 //
-// Element layout ("blocked"): a wavefront holds 64*R keys, key number e lives in
-// lane e / R, register e % R.  Small exchange distances (the most frequent ones in
-// a bitonic network) then stay inside a lane and cost no cross-lane traffic.
+// Two element layouts for 64*R keys held by a wavefront:
+//   "blocked": key number e lives in lane e / R, register e % R.  The small exchange distances
+//              of a full sort (the most frequent ones) stay inside a lane.  R a power of two.
+//   "striped": key number e lives in register e / 64, lane e % 64.  Any R; a register is a
+//              contiguous run of 64 keys, so consecutive lanes hold consecutive keys (LDS
+//              accesses by key number are conflict-free, the first k keys are the first lanes).
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -149,6 +152,35 @@ __device__ __forceinline__ void bitonic_sort_runs(uint64_t (&v)[R], int lane) {
 template <int R>
 __device__ __forceinline__ void bitonic_merge(uint64_t (&v)[R], int lane) {
     bitonic_clean<R, 32 * R>(v, lane);
+}
+
+// Striped layout: sorts 64*R keys that form one bitonic run that first rises and then falls (what
+// "element e of an ascending run against element 64*R-1-e of another" leaves behind).  R need not be
+// a power of two: the run is thought of as the upper part of P >= R registers (P a power of two) whose
+// lower P - R registers hold keys below everything - still one rising-then-falling run, and a
+// compare-exchange with such a register changes nothing, so it is left out.  First the stages between
+// registers (distances P/2 .. 1 registers), then the six lane stages inside every register.
+template <int R, int P, int D>
+__device__ __forceinline__ void striped_register_stages(uint64_t (&v)[R]) {
+    if constexpr (D >= 1) {
+        constexpr int pad = P - R;
+#pragma unroll
+        for (int i = 0; i < P; ++i)
+            if ((i & D) == 0 && i >= pad) order2(v[i - pad], v[i + D - pad]);
+        striped_register_stages<R, P, D / 2>(v);
+    }
+}
+template <int R>
+__device__ __forceinline__ void striped_merge(uint64_t (&v)[R], int lane) {
+    constexpr int P = R <= 1 ? 1 : R <= 2 ? 2 : R <= 4 ? 4 : 8;
+    static_assert(R >= 1 && R <= 8, "registers per lane");
+    striped_register_stages<R, P, P / 2>(v);
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        uint64_t one[1] = {v[r]};
+        bitonic_clean<1, 32>(one, lane);
+        v[r] = one[0];
+    }
 }
 
 }  // namespace ann
