@@ -103,8 +103,10 @@ enum {
     ANN_OPT_VISITED_HASH_BITS_BIAS = 2,    /* -4 .. 4: log2 factor on the size of the visited hash (default 0);
                                               the hash never gets smaller than the rounds need */
     ANN_OPT_MATRIX_CORE_ROUTING = 3,       /* 0: route with the plain one-wavefront-per-query kernel (default 1) */
-    ANN_OPT_LANES_PER_ROW = 4              /* lanes that share one vector row in the gather, among the built
+    ANN_OPT_LANES_PER_ROW = 4,             /* lanes that share one vector row in the gather, among the built
                                               variants (4, 8 or 32); 0 = the default choice */
+    ANN_OPT_WAVEFRONTS_PER_QUERY = 5       /* 1, 2 or 4 wavefronts work on one query (the leader keeps the list, all
+                                              share a round's gathers); 0 = chosen per call (default) */
 };
 int ann_index_set_option(ann_index_t* handle, int option, int64_t value);
 

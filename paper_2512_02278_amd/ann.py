@@ -18,7 +18,7 @@ ANN_U8, ANN_F16, ANN_F32 = 0, 1, 2
 ANN_L2, ANN_IP = 0, 1
 ANN_ENTRY_UNIFORM, ANN_ENTRY_ROUTED = 0, 1
 (ANN_OPT_CLUSTER_ORDER_MIN_QUERIES, ANN_OPT_VISITED_WINDOW_BITS, ANN_OPT_VISITED_HASH_BITS_BIAS,
- ANN_OPT_MATRIX_CORE_ROUTING, ANN_OPT_LANES_PER_ROW) = range(5)
+ ANN_OPT_MATRIX_CORE_ROUTING, ANN_OPT_LANES_PER_ROW, ANN_OPT_WAVEFRONTS_PER_QUERY) = range(6)
 ANN_STATIC_SCRATCH_BYTES = 32 * 1024 * 1024
 ANN_OK, ANN_EINVAL, ANN_EUNSUPPORTED, ANN_ENOMEM, ANN_EHIP = 0, -1, -2, -3, -4
 

@@ -22,7 +22,7 @@ namespace ann {
 // explicit specialisations live in the inst_*.hip files
 #define ANN_DECLARE(DT, METRIC, G, NCH)                                                                           \
     template <>                                                                                                  \
-    hipError_t launch_search<DT, METRIC, G, NCH>(const SearchParams&, int, unsigned, size_t, hipStream_t);        \
+    hipError_t launch_search<DT, METRIC, G, NCH>(const SearchParams&, int, int, unsigned, size_t, hipStream_t);   \
     template <>                                                                                                  \
     hipError_t launch_route<DT, METRIC, G, NCH>(const RouteParams&, hipStream_t);
 ANN_ROW_VARIANTS(ANN_DECLARE)
@@ -30,7 +30,7 @@ ANN_ROW_VARIANTS(ANN_DECLARE)
 
 struct RowVariant {
     int dtype, metric, g, nch;
-    hipError_t (*search)(const SearchParams&, int, unsigned, size_t, hipStream_t);
+    hipError_t (*search)(const SearchParams&, int, int, unsigned, size_t, hipStream_t);
     hipError_t (*route)(const RouteParams&, hipStream_t);
 };
 
@@ -70,6 +70,7 @@ struct ann_index {
     int hash_bits_bias;       // extra (or fewer) bits for the visited hash
     int window_bits;          // size of the visited bitmap over the routed clusters' ids
     int64_t cluster_order_min;  // batches of at least this many queries run grouped by cluster; < 0: never
+    int team;                   // wavefronts per query; 0: chosen per call from the batch size and the row length
     bool matrix_core_routing;
     int32_t* centroid_bias;  // DEVICE, owned: per-centroid term of the uint8 d=128 matrix-core routing, or null
     void* route_bias;        // DEVICE, owned: the same for the general matrix-core routing, or null
@@ -133,6 +134,7 @@ extern "C" int ann_index_load(const ann_index_desc_t* desc, ann_index_t** out_ha
     h->hash_bits_bias = 0;
     h->window_bits = d.entry_mode == ANN_ENTRY_ROUTED ? kDefaultWindowBits : 0;
     h->cluster_order_min = kMinQueriesForClusterOrder;
+    h->team = 0;
     h->matrix_core_routing = true;
     h->centroid_bias = nullptr;
     h->route_bias = nullptr;
@@ -212,7 +214,7 @@ int make_plan(const ann_index* h, int itopk, int width, Plan* plan, const char* 
     // words: round scratch (keys + ids, or a copy of the list), parents, window table, bitmap, hash
     const size_t scratch = 3 * (size_t)plan->cap > 128 * (size_t)kListVariants[lv][0] ? 3 * (size_t)plan->cap
                                                                                    : 128 * (size_t)kListVariants[lv][0];
-    plan->lds_bytes = sizeof(uint32_t) * (scratch + 64 + 32 + (size_t)h->window_bits / 32 + (size_t(1) << bits));
+    plan->lds_bytes = sizeof(uint32_t) * (scratch + 64 + 32 + 8 + (size_t)h->window_bits / 32 + (size_t(1) << bits));
     return ANN_OK;
 }
 
@@ -242,6 +244,11 @@ extern "C" int ann_index_set_option(ann_index_t* h, int option, int64_t value) {
             return ANN_OK;
         case ANN_OPT_MATRIX_CORE_ROUTING:
             h->matrix_core_routing = value != 0;
+            return ANN_OK;
+        case ANN_OPT_WAVEFRONTS_PER_QUERY:
+            if (value != 0 && value != 1 && value != 2 && value != 4)
+                return fail(ANN_EUNSUPPORTED, "ann_index_set_option: %lld wavefronts per query (0, 1, 2 or 4)", (long long)value);
+            h->team = (int)value;
             return ANN_OK;
         case ANN_OPT_LANES_PER_ROW: {
             const RowVariant* v = pick_variant(h->d.dtype, h->d.metric, h->row_bytes, (int)value);
@@ -350,6 +357,15 @@ extern "C" int ann_route(ann_index_t* h, const void* queries, int64_t nq, int32_
 
 namespace {
 
+// Wavefronts per query when the caller has not fixed them.  A team pays where a round's gathers are the
+// long pole and the chip is not full anyway: long rows (a wavefront covers few of them per instruction and
+// has a bounded number of loads in flight) and a batch that leaves most wavefront slots empty.
+int default_team(const ann_index_t* h, int64_t nq) {
+    if (h->row_bytes >= 1024) return 4;               // 1536-byte rows: +15 % even at 50 000 queries per launch
+    if (h->row_bytes >= 256 && nq <= 2048) return 4;  // 384-byte rows: a few percent, small batches only
+    return 1;                                         // 128-byte rows: a round's gathers are one instruction group
+}
+
 // Checks the arguments of a search and launches it; `route` is null for uniform entries.
 int search_impl(ann_index_t* h, const void* queries, int64_t nq, const int32_t* route, bool route_given, int k,
                 int itopk, int width, int max_iters, int32_t* out_ids, void* out_dists, int32_t* out_counters,
@@ -385,6 +401,7 @@ int search_impl(ann_index_t* h, const void* queries, int64_t nq, const int32_t* 
         if (e != hipSuccess) return fail(ANN_EHIP, "ann_search: launching the execution-order kernels failed: %s", hipGetErrorString(e));
     }
 
+    const int team = h->team ? h->team : default_team(h, nq);
     for (int64_t q0 = 0; q0 < nq; q0 += kMaxQueriesPerLaunch) {
         const int64_t cnt = nq - q0 < kMaxQueriesPerLaunch ? nq - q0 : kMaxQueriesPerLaunch;
         SearchParams p;
@@ -418,7 +435,7 @@ int search_impl(ann_index_t* h, const void* queries, int64_t nq, const int32_t* 
         p.out_dists = static_cast<uint32_t*>(out_dists);
         p.out_counters = out_counters;
         p.order = order;
-        const hipError_t e = h->variant->search(p, plan.list_variant, (unsigned)(8 * p.q_per_xcd), plan.lds_bytes, stream);
+        const hipError_t e = h->variant->search(p, plan.list_variant, team, (unsigned)(8 * p.q_per_xcd), plan.lds_bytes, stream);
         if (e != hipSuccess) return fail(ANN_EHIP, "ann_search: launch failed: %s", hipGetErrorString(e));
     }
     return ANN_OK;

@@ -81,9 +81,11 @@ __device__ __forceinline__ bool hash_insert(uint32_t* table, int hash_bits, uint
     }
 }
 
-__device__ __forceinline__ void lds_sync() { __syncthreads(); }  // one wavefront per workgroup
-
-template <class Row, int LPL, int CPL>
+// TEAM wavefronts serve one query (one workgroup of 64 * TEAM lanes).  Wavefront 0, the leader, owns
+// the candidate list, the visited set and the choice of parents; all wavefronts share the gathers and
+// keys of a round, which is where the time of a round with long rows goes when few queries are in
+// flight (a wavefront has only so many loads in flight; TEAM of them have TEAM times as many).
+template <class Row, int LPL, int CPL, int TEAM = 1>
 struct BeamSearch {
     static constexpr int G = Row::G;
     static constexpr int NCH = Row::NCH;
@@ -94,6 +96,9 @@ struct BeamSearch {
 
     const SearchParams& p;
     int lane;
+    int wave;        // 0 .. TEAM-1, uniform
+    uint32_t* team;  // words the wavefronts of a team exchange (TEAM > 1)
+    enum { kTeamM = 0, kTeamDone = 1, kTeamKept = 2, kTeamWorst = 4, kTeamWords = 8 };
     uint32_t* table;
     uint64_t* ckey;
     uint32_t* cid;
@@ -112,19 +117,35 @@ struct BeamSearch {
     // addresses fold into the DS instructions' immediate offsets:
     //   [0, kScratchWords)   packed keys of a round (2 words each), then its surviving ids; the same
     //                        words hold a copy of the whole list while a few keys are inserted
-    //   parents (64)  window table (32)  bitmap (window_bits / 32)  hash (1 << hash_bits)
+    //   parents (64)  window table (32)  team words (8)  bitmap (window_bits / 32)  hash (1 << hash_bits)
     static constexpr int kCap = 64 * CPL;
     static constexpr int kScratchWords = 3 * kCap > 128 * LPL ? 3 * kCap : 128 * LPL;
 
-    __device__ __forceinline__ BeamSearch(const SearchParams& p_, uint32_t* lds, int lane_) : p(p_), lane(lane_) {
+    __device__ __forceinline__ BeamSearch(const SearchParams& p_, uint32_t* lds, int lane_, int wave_)
+        : p(p_), lane(lane_), wave(wave_) {
         ckey = reinterpret_cast<uint64_t*>(lds);
         cid = lds + 2 * kCap;
         parents = lds + kScratchWords;
         wtab = parents + 64;
-        bitmap = wtab + 32;
+        team = wtab + 32;
+        bitmap = team + kTeamWords;
         table = bitmap + (p.window_bits >> 5);
         n_windows = n_table = n_dist = n_parents = n_resets = 0;
         w0_lo = w0_size = 0;
+    }
+
+    // Orders this wavefront's LDS accesses: what it wrote before is what its lanes read after.  A lone
+    // wavefront uses the workgroup barrier (which is then no more than that); in a team the leader's own
+    // steps must not wait for the other wavefronts, so it only fences (a wavefront's LDS instructions
+    // execute in the order they were issued).
+    __device__ __forceinline__ void lds_sync() const {
+        if constexpr (TEAM == 1) {
+            __syncthreads();
+        } else {
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+        }
     }
 
     __device__ __forceinline__ void clear_table() {
@@ -235,6 +256,59 @@ struct BeamSearch {
         return kept;
     }
 
+    // The same for a team: wavefront w takes the blocks of RPS * U rows number w, w + TEAM, ...  The keys
+    // that can enter the list are appended to ckey through a counter the team shares; their order in ckey
+    // is whatever the atomics give, which the merge does not depend on (it orders them).
+    __device__ __forceinline__ void score_team(int m) {
+        const int grp = lane / G;
+        const uint64_t worst = this->worst;
+        const uint8_t* const piece0 = row.lane_piece(p.vectors);
+        const uint32_t stride = (uint32_t)p.row_stride;
+        u32x4 x[U][NCH];
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int c = 0; c < NCH; ++c) x[u][c] = u32x4{0, 0, 0, 0};
+        for (int j0 = wave * (RPS * U); j0 < m; j0 += RPS * U * TEAM) {
+            uint32_t id[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                if (j0 + u * RPS >= m) break;
+                const int j = j0 + u * RPS + grp;
+                const bool live = j < m;
+                id[u] = live ? cid[j] : 0u;
+                row.reload_row(x[u], piece0 + (uint64_t)id[u] * stride, live);
+            }
+            uint64_t packed[U], b[U];
+            bool keep[U];
+            int cnt = 0;
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                b[u] = 0;
+                keep[u] = false;
+                packed[u] = 0;
+                if (j0 + u * RPS < m) {
+                    const int j = j0 + u * RPS + grp;
+                    const uint32_t okey = row.key(x[u], lane);
+                    packed[u] = ((uint64_t)okey << 32) | (uint64_t)(id[u] << 1);
+                    keep[u] = j < m && row.lg == 0 && packed[u] < worst;
+                    b[u] = __ballot(keep[u]);
+                    cnt += __builtin_popcountll(b[u]);
+                }
+            }
+            if (cnt > 0) {  // uniform
+                int base = 0;
+                if (lane == 0) base = (int)atomicAdd(&team[kTeamKept], (uint32_t)cnt);
+                base = __builtin_amdgcn_readfirstlane(base);
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    if (keep[u]) ckey[rank_below(b[u], base)] = packed[u];
+                    base += __builtin_popcountll(b[u]);
+                }
+            }
+        }
+    }
+
     // list <- itopk smallest of list U ckey[base .. base + 64*R), R registers per lane;
     // KMAX >= the number of real keys in the batch (a power of two, at most 64*R).
     template <int R, int KMAX>
@@ -331,8 +405,9 @@ struct BeamSearch {
         if (m > 0) worst = list_worst();
     }
 
-    __device__ __forceinline__ void run(int64_t qi) {
-        row.load_query(p.queries + qi * (int64_t)p.row_bytes, p.row_bytes, lane);
+    // Empty list and visited set, the windows of the routed clusters, and the entry ids (duplicates collapse
+    // in the visited set) in cid[0..returned count).
+    __device__ __forceinline__ int start(int64_t qi) {
 #pragma unroll
         for (int r = 0; r < LPL; ++r) L[r] = kInfKey;
         worst = kInfKey;
@@ -361,8 +436,6 @@ struct BeamSearch {
             n_windows = p.route_c;
         }
         lds_sync();
-
-        // entries (duplicates collapse in the visited set)
         int m = 0;
 #pragma unroll
         for (int t = 0; t < CPL; ++t) {
@@ -382,60 +455,57 @@ struct BeamSearch {
             }
             filter_into(e, valid, m);
         }
-        lds_sync();
-        m = score(m);
-        lds_sync();
-        merge_all(m);
+        return m;
+    }
 
-        const int limit = (3 << p.hash_bits) >> 2;
-        int iters = 0;
-        for (; iters < p.max_iters; ++iters) {
-            // parents: the first <= width unexpanded entries in list order.  Register r holds entries
-            // 64r .. 64r+63, so the registers are walked in order and the walk stops once `width` are found.
-            int total = 0;
+    // One round up to the gathers: marks the first <= width unexpanded list entries as expanded, reads their
+    // graph rows and leaves the ids that were never scored in cid[0..returned count); -1 if nothing is
+    // left to expand.
+    __device__ __forceinline__ int expand() {
+        // Register r holds entries 64r .. 64r+63, so the registers are walked in order and the walk stops
+        // once `width` parents are found.
+        int total = 0;
 #pragma unroll
-            for (int r = 0; r < LPL; ++r) {
-                if (total < p.width) {  // uniform
-                    uint32_t ex;  // taken in the 32-bit low word (the compiler otherwise widens the test to the whole key)
-                    asm("v_and_b32 %0, 1, %1" : "=v"(ex) : "v"((uint32_t)L[r]));
-                    const bool un = ex == 0;
-                    const uint64_t b = __ballot(un);
-                    const int rank = rank_below(b, total);
-                    const bool take = un && rank < p.width;
-                    if (take) parents[rank] = (uint32_t)L[r] >> 1;
-                    L[r] |= (uint64_t)(take ? 1u : 0u);
-                    total += __builtin_popcountll(b);
-                }
+        for (int r = 0; r < LPL; ++r) {
+            if (total < p.width) {  // uniform
+                uint32_t ex;  // taken in the 32-bit low word (the compiler otherwise widens the test to the whole key)
+                asm("v_and_b32 %0, 1, %1" : "=v"(ex) : "v"((uint32_t)L[r]));
+                const bool un = ex == 0;
+                const uint64_t b = __ballot(un);
+                const int rank = rank_below(b, total);
+                const bool take = un && rank < p.width;
+                if (take) parents[rank] = (uint32_t)L[r] >> 1;
+                L[r] |= (uint64_t)(take ? 1u : 0u);
+                total += __builtin_popcountll(b);
             }
-            if (total == 0) break;
-            const int np = total < p.width ? total : p.width;
-            n_parents += np;
-            if (n_table + np * p.degree > limit) reset_table();
-            lds_sync();
-
-            // neighbour ids of the parents, 64 per step, all loads issued first
-            const int nref = np * p.degree;
-            int32_t nb[CPL];
-#pragma unroll
-            for (int t = 0; t < CPL; ++t) {
-                const int s = t * 64 + lane;
-                nb[t] = -1;
-                if (s < nref) {
-                    const int pi = (int)(((uint32_t)s * p.degree_inv) >> 20);
-                    // unsigned 32 x 32 -> 64 bit: one multiply-add
-                    nb[t] = p.graph[(uint64_t)parents[pi] * (uint32_t)p.degree + (uint32_t)(s - pi * p.degree)];
-                }
-            }
-            m = 0;
-#pragma unroll
-            for (int t = 0; t < CPL; ++t) filter_into(nb[t], t * 64 + lane < nref, m);
-            lds_sync();
-            m = score(m);
-            lds_sync();
-            merge_all(m);
         }
+        if (total == 0) return -1;
+        const int np = total < p.width ? total : p.width;
+        n_parents += np;
+        if (n_table + np * p.degree > ((3 << p.hash_bits) >> 2)) reset_table();
+        lds_sync();
 
-        // first k list entries
+        // neighbour ids of the parents, 64 per step, all loads issued first
+        const int nref = np * p.degree;
+        int32_t nb[CPL];
+#pragma unroll
+        for (int t = 0; t < CPL; ++t) {
+            const int s = t * 64 + lane;
+            nb[t] = -1;
+            if (s < nref) {
+                const int pi = (int)(((uint32_t)s * p.degree_inv) >> 20);
+                // unsigned 32 x 32 -> 64 bit: one multiply-add
+                nb[t] = p.graph[(uint64_t)parents[pi] * (uint32_t)p.degree + (uint32_t)(s - pi * p.degree)];
+            }
+        }
+        int m = 0;
+#pragma unroll
+        for (int t = 0; t < CPL; ++t) filter_into(nb[t], t * 64 + lane < nref, m);
+        return m;
+    }
+
+    // First k list entries and the counters.
+    __device__ __forceinline__ void finish(int64_t qi, int iters) {
 #pragma unroll
         for (int r = 0; r < LPL; ++r) {
             const int e = r * 64 + lane;
@@ -453,20 +523,86 @@ struct BeamSearch {
             c[3] = n_resets;
         }
     }
+
+    __device__ __forceinline__ void run(int64_t qi) {
+        row.load_query(p.queries + qi * (int64_t)p.row_bytes, p.row_bytes, lane);
+        if constexpr (TEAM > 1) {
+            run_team(qi);
+            return;
+        }
+        int m = start(qi);
+        lds_sync();
+        m = score(m);
+        lds_sync();
+        merge_all(m);
+        int iters = 0;
+        for (; iters < p.max_iters; ++iters) {
+            m = expand();
+            if (m < 0) break;
+            lds_sync();
+            m = score(m);
+            lds_sync();
+            merge_all(m);
+        }
+        finish(qi, iters);
+    }
+
+    // The leader tells the team what the next scoring step works on.
+    __device__ __forceinline__ void publish(int m, int done) {
+        if (lane == 0) {
+            team[kTeamM] = (uint32_t)m;
+            team[kTeamDone] = (uint32_t)done;
+            team[kTeamKept] = 0u;
+            team[kTeamWorst] = (uint32_t)worst;
+            team[kTeamWorst + 1] = (uint32_t)(worst >> 32);
+        }
+    }
+
+    // Two workgroup barriers per round: before the scoring step (the leader has left the round's ids, their
+    // count and the list's worst key in LDS) and after it (every wavefront's keys are in ckey).  Between the
+    // second barrier and the next first one only the leader works: merge, parents, graph rows, visited filter.
+    // Every wavefront leaves the loop in the same round, on the flag the leader publishes.
+    __device__ __forceinline__ void run_team(int64_t qi) {
+        const bool leader = wave == 0;
+        int iters = 0;
+        if (leader) {
+            const int m = start(qi);
+            lds_sync();
+            publish(m, 0);
+        }
+        for (;;) {
+            __syncthreads();
+            const int m = (int)team[kTeamM];
+            if (team[kTeamDone] != 0u) break;
+            worst = ((uint64_t)team[kTeamWorst + 1] << 32) | team[kTeamWorst];
+            score_team(m);
+            __syncthreads();
+            if (leader) {
+                n_dist += m;
+                merge_all((int)team[kTeamKept]);
+                int next = -1;
+                if (iters < p.max_iters) next = expand();
+                if (next >= 0) ++iters;
+                lds_sync();
+                publish(next < 0 ? 0 : next, next < 0 ? 1 : 0);
+            }
+        }
+        if (leader) finish(qi, iters);
+    }
 };
 
 // Workgroup b runs on XCD b % 8 (round-robin dispatch), so consecutive queries are
 // kept on one XCD and its L2: query = (b % 8) * q_per_xcd + b / 8.
 // The small uint8 variants are asked to fit 7 wavefronts per SIMD (72 vector registers; 8 would need spills):
 // with about 5.5 KB of LDS per query that is also what a compute unit's LDS holds, 28 queries in flight.
-template <class Row, int LPL, int CPL>
-__global__ void __launch_bounds__(64, (Row::kDtype == kU8 && LPL <= 4 && CPL <= 2) ? 7 : 1)
+template <class Row, int LPL, int CPL, int TEAM>
+__global__ void __launch_bounds__(64 * TEAM, (TEAM == 1 && Row::kDtype == kU8 && LPL <= 4 && CPL <= 2) ? 7 : 1)
     beam_search_kernel(const SearchParams p) {
     extern __shared__ uint32_t lds[];
     const int64_t b = blockIdx.x;
     const int64_t local = (b & 7) * p.q_per_xcd + (b >> 3);
-    if (local >= p.q_count) return;
-    BeamSearch<Row, LPL, CPL> s(p, lds, lane_id());
+    if (local >= p.q_count) return;  // the whole workgroup
+    BeamSearch<Row, LPL, CPL, TEAM> s(p, lds, lane_id(), TEAM == 1 ? 0 : __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)));
     s.run(p.order ? (int64_t)p.order[p.q_base + local] : p.q_base + local);
 }
 

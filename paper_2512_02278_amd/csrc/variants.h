@@ -23,25 +23,38 @@ namespace ann {
 constexpr int kListVariants[][2] = {{1, 1}, {2, 2}, {3, 2}, {4, 2}, {4, 4}, {4, 8}, {8, 8}};
 constexpr int kNumListVariants = 7;
 
+// Wavefronts per query a launch may use (see BeamSearch).
+constexpr int kTeamSizes[] = {1, 2, 4};
+constexpr int kNumTeamSizes = 3;
+
 template <int DT, int METRIC, int G, int NCH>
-hipError_t launch_search(const SearchParams& p, int list_variant, unsigned grid, size_t lds_bytes, hipStream_t stream);
+hipError_t launch_search(const SearchParams& p, int list_variant, int team, unsigned grid, size_t lds_bytes, hipStream_t stream);
 
 template <int DT, int METRIC, int G, int NCH>
 hipError_t launch_route(const RouteParams& p, hipStream_t stream);
 
+#define ANN_LAUNCH_LIST(LPL, CPL)                                                                                         \
+    switch (team) {                                                                                                       \
+        case 1: hipLaunchKernelGGL((beam_search_kernel<Row, LPL, CPL, 1>), dim3(grid), dim3(64), lds_bytes, stream, p); break;  \
+        case 2: hipLaunchKernelGGL((beam_search_kernel<Row, LPL, CPL, 2>), dim3(grid), dim3(128), lds_bytes, stream, p); break; \
+        case 4: hipLaunchKernelGGL((beam_search_kernel<Row, LPL, CPL, 4>), dim3(grid), dim3(256), lds_bytes, stream, p); break; \
+        default: return hipErrorInvalidValue;                                                                             \
+    }                                                                                                                     \
+    break;
+
 #define ANN_DEFINE_ROW_VARIANT(DT, METRIC, G, NCH)                                                              \
     template <>                                                                                                 \
-    hipError_t launch_search<DT, METRIC, G, NCH>(const SearchParams& p, int list_variant, unsigned grid,        \
+    hipError_t launch_search<DT, METRIC, G, NCH>(const SearchParams& p, int list_variant, int team, unsigned grid, \
                                                  size_t lds_bytes, hipStream_t stream) {                        \
         using Row = RowOps<DT, METRIC, G, NCH>;                                                                 \
         switch (list_variant) {                                                                                 \
-            case 0: hipLaunchKernelGGL((beam_search_kernel<Row, 1, 1>), dim3(grid), dim3(64), lds_bytes, stream, p); break; \
-            case 1: hipLaunchKernelGGL((beam_search_kernel<Row, 2, 2>), dim3(grid), dim3(64), lds_bytes, stream, p); break; \
-            case 2: hipLaunchKernelGGL((beam_search_kernel<Row, 3, 2>), dim3(grid), dim3(64), lds_bytes, stream, p); break; \
-            case 3: hipLaunchKernelGGL((beam_search_kernel<Row, 4, 2>), dim3(grid), dim3(64), lds_bytes, stream, p); break; \
-            case 4: hipLaunchKernelGGL((beam_search_kernel<Row, 4, 4>), dim3(grid), dim3(64), lds_bytes, stream, p); break; \
-            case 5: hipLaunchKernelGGL((beam_search_kernel<Row, 4, 8>), dim3(grid), dim3(64), lds_bytes, stream, p); break; \
-            case 6: hipLaunchKernelGGL((beam_search_kernel<Row, 8, 8>), dim3(grid), dim3(64), lds_bytes, stream, p); break; \
+            case 0: ANN_LAUNCH_LIST(1, 1)                                                                       \
+            case 1: ANN_LAUNCH_LIST(2, 2)                                                                       \
+            case 2: ANN_LAUNCH_LIST(3, 2)                                                                       \
+            case 3: ANN_LAUNCH_LIST(4, 2)                                                                       \
+            case 4: ANN_LAUNCH_LIST(4, 4)                                                                       \
+            case 5: ANN_LAUNCH_LIST(4, 8)                                                                       \
+            case 6: ANN_LAUNCH_LIST(8, 8)                                                                       \
             default: return hipErrorInvalidValue;                                                               \
         }                                                                                                       \
         return hipGetLastError();                                                                               \

@@ -189,14 +189,19 @@ def queries_near(rng, x, nq, dt):
     (33, 2, 24, 33, 7),      # odd sizes, k = itopk, degree not a power of two
     (128, 4, 32, 10, 32),    # the 1M / 100M configs' shape
     (100, 3, 40, 16, 100),   # batch 120, 100 entries
-    (192, 4, 32, 10, 32),
+    (192, 4, 32, 10, 32),    # three registers per lane
+    (184, 4, 32, 10, 32),    # the list size the 100M benchmark ends up with
+    (130, 2, 32, 130, 32),   # three registers, nearly empty last one, k = itopk
     (256, 4, 32, 10, 32),    # a full list of 4 registers per lane with a 2-register batch
     (256, 4, 64, 10, 32),    # the Deep-like config's shape
     (256, 8, 64, 100, 32),   # the text-like config's shape: 512 neighbours per round
     (512, 2, 48, 50, 500),
     (1, 1, 16, 1, 1),        # a plain greedy walk
 ])
-def test_uint8_bit_exact_across_list_variants(oracle, torch_cuda, itopk, width, degree, k, n_entry):
+@pytest.mark.parametrize("team", [1, 2, 4])
+def test_uint8_bit_exact_across_list_variants(oracle, torch_cuda, itopk, width, degree, k, n_entry, team):
+    from paper_2512_02278_amd import ann
+
     rng = np.random.default_rng(itopk * 131 + width)
     x, cen, off = clustered(rng, 6000, 128, "u8")
     g = knn_graph(x, degree)
@@ -205,9 +210,10 @@ def test_uint8_bit_exact_across_list_variants(oracle, torch_cuda, itopk, width, 
     dup = rng.random(g.shape[0]) < 0.1
     g[dup, 1] = g[dup, 0]                                    # the same neighbour twice in a row
     q = queries_near(rng, x, 150, "u8")
-    check_exact(oracle, torch_cuda, x, g, q, k, itopk, width, 80, n_entry=n_entry, seed=itopk)
+    opts = {ann.ANN_OPT_WAVEFRONTS_PER_QUERY: team}
+    check_exact(oracle, torch_cuda, x, g, q, k, itopk, width, 80, n_entry=n_entry, seed=itopk, options=opts)
     check_exact(oracle, torch_cuda, x, g, q, k, itopk, width, 80, n_entry=n_entry, seed=itopk, entry_mode=1,
-                centroids=cen, offsets=off, route_c=3)
+                centroids=cen, offsets=off, route_c=3, options=opts)
 
 
 def test_uint8_heavy_ties_and_inner_product(oracle, torch_cuda):
@@ -229,7 +235,8 @@ def test_uint8_dims_and_padded_rows(oracle, torch_cuda, dim):
     check_exact(oracle, torch_cuda, x, g, q, 10, 64, 2, 40, n_entry=8, seed=1)
 
 
-def test_small_visited_hash_forces_resets(oracle, torch_cuda):
+@pytest.mark.parametrize("team", [1, 2])
+def test_small_visited_hash_forces_resets(oracle, torch_cuda, team):
     """Without the bitmap and with the smallest hash the kernel forgets visited nodes every
     few rounds; the result must not change, only more rows are gathered."""
     rng = np.random.default_rng(77)
@@ -240,7 +247,8 @@ def test_small_visited_hash_forces_resets(oracle, torch_cuda):
 
     gc, oc = check_exact(oracle, torch_cuda, x, g, q, 10, 128, 4, 100, n_entry=32, seed=2, entry_mode=1,
                          centroids=cen, offsets=off, route_c=1,
-                         options={ann.ANN_OPT_VISITED_HASH_BITS_BIAS: -1, ann.ANN_OPT_VISITED_WINDOW_BITS: 0})
+                         options={ann.ANN_OPT_VISITED_HASH_BITS_BIAS: -1, ann.ANN_OPT_VISITED_WINDOW_BITS: 0,
+                                  ann.ANN_OPT_WAVEFRONTS_PER_QUERY: team})
     assert gc[:, 3].max() >= 1 and (gc[:, 1] > oc["n_dist"]).any()
 
 
@@ -310,20 +318,24 @@ def test_route_ids_outside_the_clusters_are_ignored(oracle, torch_cuda):
         assert np.array_equal(gi[~bad], oi[~bad]) and np.array_equal(gd[~bad], od[~bad])
 
 
-def test_edge_cases(oracle, torch_cuda):
+@pytest.mark.parametrize("team", [1, 2, 4])
+def test_edge_cases(oracle, torch_cuda, team):
+    from paper_2512_02278_amd import ann
+
+    opts = {ann.ANN_OPT_WAVEFRONTS_PER_QUERY: team}
     # one node, no edges; fewer reachable nodes than k; a single query; max_iters = 0
     x = np.full((1, 128), 7, np.uint8)
     g = np.full((1, 4), -1, np.int32)
     q = np.zeros((1, 128), np.uint8)
-    check_exact(oracle, torch_cuda, x, g, q, 5, 8, 1, 10, n_entry=3, seed=1)
+    check_exact(oracle, torch_cuda, x, g, q, 5, 8, 1, 10, n_entry=3, seed=1, options=opts)
     rng = np.random.default_rng(1)
     x = rng.integers(0, 256, (40, 128), dtype=np.uint8)
     g = np.full((40, 4), -1, np.int32)
     q = rng.integers(0, 256, (9, 128), dtype=np.uint8)
-    check_exact(oracle, torch_cuda, x, g, q, 10, 16, 2, 10, n_entry=4, seed=2)   # no edges: only entries
+    check_exact(oracle, torch_cuda, x, g, q, 10, 16, 2, 10, n_entry=4, seed=2, options=opts)   # no edges: only entries
     g = rng.integers(0, 40, (40, 4), dtype=np.int32)
-    check_exact(oracle, torch_cuda, x, g, q, 10, 16, 2, 0, n_entry=4, seed=2)    # max_iters = 0
-    check_exact(oracle, torch_cuda, x, g, q, 40, 64, 3, 200, n_entry=4, seed=2)  # itopk above n
+    check_exact(oracle, torch_cuda, x, g, q, 10, 16, 2, 0, n_entry=4, seed=2, options=opts)    # max_iters = 0
+    check_exact(oracle, torch_cuda, x, g, q, 40, 64, 3, 200, n_entry=4, seed=2, options=opts)  # itopk above n
 
 
 # ----------------------------------------------------------------------------- float data
@@ -338,7 +350,10 @@ MIN_IDENTICAL = {"f32": 0.99, "f16": 0.95}  # share of queries whose id lists eq
     ("f16", 768, 0, 128, 4, 32, 10),
     ("f16", 64, 0, 64, 1, 16, 10),
 ])
-def test_float_parity(oracle, torch_cuda, dt, dim, metric, itopk, width, degree, k):
+@pytest.mark.parametrize("team", [1, 4])
+def test_float_parity(oracle, torch_cuda, dt, dim, metric, itopk, width, degree, k, team):
+    from paper_2512_02278_amd import ann
+
     rng = np.random.default_rng(dim + metric)
     x, cen, off = clustered(rng, 4000, dim, dt)
     if metric == 1:
@@ -346,7 +361,7 @@ def test_float_parity(oracle, torch_cuda, dt, dim, metric, itopk, width, degree,
     g = knn_graph(x, degree, metric)
     q = queries_near(rng, x, 120, dt)
     same = check_float(oracle, torch_cuda, x, g, q, k, itopk, width, 100, TOL[dt], MIN_IDENTICAL[dt], metric=metric,
-                       n_entry=32, seed=4)
+                       n_entry=32, seed=4, options={ann.ANN_OPT_WAVEFRONTS_PER_QUERY: team})
     print(f"{dt} dim={dim} metric={metric}: {same:.3f} of the queries have identical id lists")
 
 
