@@ -483,12 +483,22 @@ def search_roofline(prof: dict, leg: str, sha: str, nq: int, kernel_ms: float, g
                          "dram_read_bytes": prof.get(f"{leg}.dram_read_bytes")})
         valu = prof[f"{leg}.valu_insts"]  # wavefront instructions per launch
         tops = valu * 64 / sec / 1e12
-        out = {"bound": "alu", "kernel": "beam_search_kernel", "achieved": round(tops, 2), "peak": round(VALU_PEAK_TOPS, 2),
-               "unit": "TOP/s", "frac": round(tops / VALU_PEAK_TOPS, 4), "traffic": traffic, "kernel_ms": round(kernel_ms, 3),
-               "valu_insts_per_query": round(valu / nq, 1), "valu_busy_frac_by_counter": prof.get(f"{leg}.valu_busy_frac"),
-               "note": "vector-ALU issue: vector instructions the launch issued (rocprofv3 SQ_INSTS_VALU) x 64 lanes / kernel "
-                       "time, against 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz; the launch is bound by instruction issue, "
-                       "not by bytes (see hbm)"}
+        alu_view = {"achieved": round(tops, 2), "peak": round(VALU_PEAK_TOPS, 2), "unit": "TOP/s", "frac": round(tops / VALU_PEAK_TOPS, 4),
+                    "valu_insts_per_query": round(valu / nq, 1), "valu_busy_frac_by_counter": prof.get(f"{leg}.valu_busy_frac"),
+                    "note": "vector-ALU issue: vector instructions the launch issued (rocprofv3 SQ_INSTS_VALU) x 64 lanes / kernel time, "
+                            "against 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz"}
+        # the binding resource is the one that is nearer to its peak
+        if alu_view["frac"] >= hbm_view["frac"]:
+            out = {"bound": "alu", "kernel": "beam_search_kernel", "achieved": alu_view["achieved"], "peak": alu_view["peak"],
+                   "unit": "TOP/s", "frac": alu_view["frac"], "traffic": traffic, "kernel_ms": round(kernel_ms, 3),
+                   "note": "the launch is bound by vector-ALU instruction issue, not by bytes: most gathers of the grouped batch "
+                           "hit L2 (see hbm for the byte view, drawn_order for the HBM-bound run of the same kernel)"}
+        else:
+            out = {"bound": "hbm", "kernel": "beam_search_kernel", "achieved": hbm_view["achieved"], "peak": HBM_PEAK_GBPS,
+                   "unit": "GB/s", "frac": hbm_view["frac"], "traffic": traffic, "kernel_ms": round(kernel_ms, 3),
+                   "note": "the launch is bound by bytes: achieved = measured traffic between L2 and the fabric / kernel time (the "
+                           "bytes the kernel gathers, gathered_bytes_per_launch, are more: the rest were L2 hits)"}
+        out["alu"] = alu_view
     elif drawn is not None:
         out = dict(drawn, kernel="beam_search_kernel",
                    note="no current instruction counters for the grouped launch: this is the drawn-order launch of the same "
