@@ -6,8 +6,8 @@
 
 namespace ann {
 
-// Entries of the per-centroid bias array: n_clusters rounded up to whole pairs of 32-row tiles.
-inline int route_mfma_padded(int n_clusters) { return (n_clusters + 63) / 64 * 64; }
+// Entries of the per-centroid bias array: n_clusters rounded up to whole tiles of 128 rows.
+inline int route_mfma_padded(int n_clusters) { return (n_clusters + 127) / 128 * 128; }
 
 // bias (4 bytes per entry: int32 for uint8 data, float otherwise): the per-centroid term of the
 // score; padding entries get a value that never wins.

@@ -9,12 +9,12 @@
 // adds -128*sum(c') per centroid, which goes into the bias); fp16 / fp32 operands accumulate in
 // fp32 on v_mfma_f32_32x32x16_f16 / v_mfma_f32_32x32x2_f32.
 //
-// A wavefront owns 64 queries (two operand sets of 32) and walks the centroids 64 at a time
-// (two sets of 32): four 32x32 accumulator tiles, and per 16-byte piece of the rows two loads
-// of each operand feed four matrix instructions.  Operands stream from L1/L2; nothing is staged
-// in LDS, and the rows can be of any length.  In a 32x32 result a lane holds 16 centroids of one
-// query, so a query's best list lives in two lanes and is merged once at the end.  Rows are
-// visited in ascending cluster order, so a strict "<" keeps the lower index among equal scores.
+// A wavefront owns a 64 x 64 block of scores (two operand sets of 32 rows on either side): four 32x32
+// accumulator tiles, and per 16-byte piece of the rows two reads of each operand feed four matrix
+// instructions.  Operand chunks are staged in LDS by the workgroup (see the kernel); the rows can be of any
+// length.  In a 32x32 result a lane holds 16 centroids of one query, so a query's best candidates live in a few
+// lanes' registers and are merged once at the end.  A lane visits its rows in ascending cluster order, so a
+// strict "<" keeps the lower index among equal scores, and the final merge compares (score, index) words.
 #include <hip/hip_runtime.h>
 
 #include "route_mfma.h"
@@ -113,30 +113,43 @@ __global__ void __launch_bounds__(256) route_bias_kernel(const uint8_t* centroid
     }
 }
 
+// One workgroup: 128 queries against 128 centroids at a time, four wavefronts in a 2 x 2 arrangement, each
+// owning a 64 x 64 block of scores (2 x 2 result tiles of 32 x 32).  The rows are walked in chunks of 64 bytes;
+// a chunk of both operands (128 rows x 64 bytes each) is staged in LDS once per workgroup, piece-major
+// ([16-byte piece][row], one unit of padding per piece so that the staging writes spread over the banks),
+// which is the order the matrix instruction consumes: lane (row % 32, half) reads consecutive 16-byte units.
+// The next chunk travels from L2 to registers while the current one is multiplied; two LDS buffers, one
+// barrier per chunk.  (Streaming the operands straight from L1/L2 in the instruction's layout - 32 rows x 32
+// bytes per load - left this kernel at a twelfth of the fp16 matrix rate.)
 template <int DT, int METRIC, int RC>
 __global__ void __launch_bounds__(256) route_mfma_kernel(const uint8_t* __restrict__ centroids,
                                                          const void* __restrict__ bias_in, int n_clusters,
                                                          int row_bytes, const uint8_t* __restrict__ queries,
                                                          int64_t nq, int32_t* __restrict__ out,
-                                                         uint64_t* __restrict__ partial, int pairs_per_slice) {
-    // blockIdx.y = slice of the centroid tile pairs this workgroup walks; with several slices the
-    // best words of a slice go to partial[q][slice][RC] and route_merge_kernel finishes the job
+                                                         uint64_t* __restrict__ partial, int tiles_per_slice) {
+    // blockIdx.y = slice of the 128-centroid tiles this workgroup walks; with several slices the best words
+    // of a slice go to partial[q][slice][RC] and route_merge_kernel finishes the job
     typedef Mma<DT> M;
     typedef typename M::acc_t acc_t;
     typedef typename M::score_t score_t;
-    __shared__ uint64_t pool[4][64][2][RC];
+    constexpr int kRows = 128, kPieces = 4, kPieceStride = kRows + 1;
+    constexpr int kOperand = kPieces * kPieceStride;  // 16-byte units of one operand chunk
+    __shared__ v4i smem[4 * kOperand];                // [buffer 0 / 1][centroids, queries]; afterwards the pool of best lists
+    static_assert(sizeof(v4i) * 4 * kOperand >= sizeof(uint64_t) * kRows * 4 * RC, "the pool reuses the staging buffers");
     const score_t* bias = static_cast<const score_t*>(bias_in);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wq = wave >> 1, wc = wave & 1;  // which 64 queries / which 64 centroids of the tile
     const int col = lane & 31, half = lane >> 5;
-    const int64_t q0 = ((int64_t)blockIdx.x * 4 + wave) * 64;
-    if (q0 >= nq) return;  // whole wavefront; no block-wide barrier is used below
+    const int64_t q0 = (int64_t)blockIdx.x * kRows;
 
-    const uint8_t* qrow[2];
+    // staging: thread x moves piece x % 4 of rows x / 4 and x / 4 + 64 (four threads read 64 contiguous bytes)
+    const int st_piece = threadIdx.x & 3, st_row = threadIdx.x >> 2;
+    const uint8_t* qsrc[2];
 #pragma unroll
-    for (int s = 0; s < 2; ++s) {
-        int64_t q = q0 + s * 32 + col;
+    for (int i = 0; i < 2; ++i) {
+        int64_t q = q0 + st_row + 64 * i;
         if (q >= nq) q = nq - 1;
-        qrow[s] = queries + q * row_bytes + half * 16;
+        qsrc[i] = queries + q * row_bytes + st_piece * 16;
     }
     score_t best_s[2][RC];
     int32_t best_i[2][RC];
@@ -148,17 +161,37 @@ __global__ void __launch_bounds__(256) route_mfma_kernel(const uint8_t* __restri
             best_i[s][r] = 0x7fffffff;
         }
 
-    const int pieces = row_bytes / 32;  // 16-byte pieces per lane and row
-    const int all_pairs = (n_clusters + 63) / 64;
-    const int n_pairs = min(all_pairs, (int)(blockIdx.y + 1) * pairs_per_slice);
-    for (int cp = blockIdx.y * pairs_per_slice; cp < n_pairs; ++cp) {
-        const uint8_t* arow[2];
+    const int chunks = (row_bytes + 63) / 64;
+    const int all_tiles = (n_clusters + kRows - 1) / kRows;
+    const int tile_end = min(all_tiles, (int)(blockIdx.y + 1) * tiles_per_slice);
+    const v4i zero = v4i{0, 0, 0, 0};
+    for (int ct = blockIdx.y * tiles_per_slice; ct < tile_end; ++ct) {
+        const uint8_t* csrc[2];
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
-            int r = cp * 64 + i * 32 + col;
-            if (r >= n_clusters) r = n_clusters - 1;
-            arow[i] = centroids + (int64_t)r * row_bytes + half * 16;
+            int r = ct * kRows + st_row + 64 * i;
+            if (r >= n_clusters) r = n_clusters - 1;  // its bias never wins
+            csrc[i] = centroids + (int64_t)r * row_bytes + st_piece * 16;
         }
+        v4i ra[2], rb[2];
+        auto fetch = [&](int ch) {
+            const int off = ch * 64;
+            const bool ok = off + st_piece * 16 < row_bytes;  // rows are multiples of 32 bytes: the last chunk may be half empty
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                ra[i] = ok ? M::prep(*reinterpret_cast<const v4i*>(csrc[i] + off)) : zero;
+                rb[i] = ok ? M::prep(*reinterpret_cast<const v4i*>(qsrc[i] + off)) : zero;
+            }
+        };
+        auto stage = [&](int buf) {
+            v4i* a = smem + buf * 2 * kOperand;
+            v4i* b = a + kOperand;
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                a[st_piece * kPieceStride + st_row + 64 * i] = ra[i];
+                b[st_piece * kPieceStride + st_row + 64 * i] = rb[i];
+            }
+        };
         acc_t acc[2][2];
 #pragma unroll
         for (int i = 0; i < 2; ++i)
@@ -166,21 +199,32 @@ __global__ void __launch_bounds__(256) route_mfma_kernel(const uint8_t* __restri
             for (int s = 0; s < 2; ++s)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) acc[i][s][v] = 0;
-        for (int t = 0; t < pieces; ++t) {
-            v4i a[2], b[2];
+        fetch(0);
+        stage(0);
+        __syncthreads();
+        for (int ch = 0; ch < chunks; ++ch) {
+            if (ch + 1 < chunks) fetch(ch + 1);
+            const v4i* a_chunk = smem + (ch & 1) * 2 * kOperand;
+            const v4i* b_chunk = a_chunk + kOperand;
 #pragma unroll
-            for (int i = 0; i < 2; ++i) a[i] = M::prep(*reinterpret_cast<const v4i*>(arow[i] + t * 32));
+            for (int t = 0; t < 2; ++t) {
+                v4i a[2], b[2];
 #pragma unroll
-            for (int s = 0; s < 2; ++s) b[s] = M::prep(*reinterpret_cast<const v4i*>(qrow[s] + t * 32));
+                for (int i = 0; i < 2; ++i) a[i] = a_chunk[(2 * t + half) * kPieceStride + wc * 64 + i * 32 + col];
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
+                for (int s = 0; s < 2; ++s) b[s] = b_chunk[(2 * t + half) * kPieceStride + wq * 64 + s * 32 + col];
 #pragma unroll
-                for (int s = 0; s < 2; ++s) M::mma(acc[i][s], a[i], b[s]);
+                for (int i = 0; i < 2; ++i)
+#pragma unroll
+                    for (int s = 0; s < 2; ++s) M::mma(acc[i][s], a[i], b[s]);
+            }
+            if (ch + 1 < chunks) stage((ch + 1) & 1);
+            __syncthreads();
         }
         // result element v of a lane is row 8 (v / 4) + 4 half + v % 4 of its 32-row tile
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
-            const int base = cp * 64 + i * 32;
+            const int base = ct * kRows + wc * 64 + i * 32;
             score_t bs[16];
 #pragma unroll
             for (int v = 0; v < 16; ++v) bs[v] = bias[base + 8 * (v / 4) + 4 * half + (v % 4)];
@@ -210,28 +254,38 @@ __global__ void __launch_bounds__(256) route_mfma_kernel(const uint8_t* __restri
         }
     }
 
-    // the two lanes of a query merge their ascending lists through LDS
+    // A query's candidates sit in four ascending lists: two lanes (halves) in each of the two wavefronts that
+    // hold its row of the tile.  They meet in LDS (the staging buffers are free now) and one thread per
+    // query merges them.
+    uint64_t* pool = reinterpret_cast<uint64_t*>(smem);  // [query 0..127][list 0..3][RC]
 #pragma unroll
     for (int s = 0; s < 2; ++s)
 #pragma unroll
         for (int r = 0; r < RC; ++r)
-            pool[wave][s * 32 + col][half][r] = ((uint64_t)M::ordered(best_s[s][r]) << 32) | (uint32_t)best_i[s][r];
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    const int64_t q = q0 + lane;  // every lane merges one query
-    if (q < nq) {
-        int ia = 0, ib = 0;
+            pool[((wq * 64 + s * 32 + col) * 4 + wc * 2 + half) * RC + r] =
+                ((uint64_t)M::ordered(best_s[s][r]) << 32) | (uint32_t)best_i[s][r];
+    __syncthreads();
+    const int64_t q = q0 + threadIdx.x;
+    if (threadIdx.x < kRows && q < nq) {
+        const uint64_t* mine = pool + threadIdx.x * 4 * RC;
+        int at[4] = {0, 0, 0, 0};
         for (int r = 0; r < RC; ++r) {
-            const uint64_t x = ia < RC ? pool[wave][lane][0][ia] : ~0ull;
-            const uint64_t y = ib < RC ? pool[wave][lane][1][ib] : ~0ull;
-            const bool take_x = x < y;
+            uint64_t best = ~0ull;
+            int from = 0;
+#pragma unroll
+            for (int l = 0; l < 4; ++l) {
+                const uint64_t x = at[l] < RC ? mine[l * RC + at[l]] : ~0ull;
+                if (x < best) {
+                    best = x;
+                    from = l;
+                }
+            }
+#pragma unroll
+            for (int l = 0; l < 4; ++l) at[l] += from == l ? 1 : 0;
             if (gridDim.y == 1)
-                out[q * RC + r] = (int32_t)(uint32_t)(take_x ? x : y);
+                out[q * RC + r] = (int32_t)(uint32_t)best;
             else
-                partial[(q * gridDim.y + blockIdx.y) * RC + r] = take_x ? x : y;
-            ia += take_x ? 1 : 0;
-            ib += take_x ? 0 : 1;
+                partial[(q * gridDim.y + blockIdx.y) * RC + r] = best;
         }
     }
 }
@@ -271,20 +325,29 @@ hipError_t launch_route_merge(int route_c, const uint64_t* partial, int slices, 
     return hipGetLastError();
 }
 
-int route_mfma_slices(int n_clusters, int64_t nq) { return route_slices((n_clusters + 63) / 64, 4, nq); }
+// Small batches leave most CUs idle when every workgroup walks all centroids, so the centroid range is cut into
+// slices (grid.y): about 512 workgroups of 128 queries, each slice at least two tiles of 128 centroids, at most 64.
+int route_mfma_slices(int n_clusters, int64_t nq) {
+    const int64_t groups = (nq + 127) / 128;
+    const int tiles = (n_clusters + 127) / 128;
+    int64_t s = 512 / groups;
+    if (s > tiles / 2) s = tiles / 2;
+    if (s > 64) s = 64;
+    return s < 1 ? 1 : (int)s;
+}
 
 template <int DT, int METRIC>
 static hipError_t launch_rc(int rc, const uint8_t* centroids, const void* bias, int n_clusters, int row_bytes,
                             const uint8_t* queries, int64_t nq, int32_t* out, uint64_t* partial, int slices,
                             hipStream_t stream) {
-    const int all_pairs = (n_clusters + 63) / 64;
-    const int pairs_per_slice = (all_pairs + slices - 1) / slices;
-    slices = (all_pairs + pairs_per_slice - 1) / pairs_per_slice;  // no slice may start beyond the last pair
-    const dim3 grid((unsigned)((nq + 255) / 256), (unsigned)slices), block(256);
+    const int all_tiles = (n_clusters + 127) / 128;
+    const int tiles_per_slice = (all_tiles + slices - 1) / slices;
+    slices = (all_tiles + tiles_per_slice - 1) / tiles_per_slice;  // no slice may start beyond the last tile
+    const dim3 grid((unsigned)((nq + 127) / 128), (unsigned)slices), block(256);
 #define ANN_RC(N)                                                                                                 \
     case N:                                                                                                       \
         hipLaunchKernelGGL((route_mfma_kernel<DT, METRIC, N>), grid, block, 0, stream, centroids, bias, n_clusters, \
-                           row_bytes, queries, nq, out, partial, pairs_per_slice);                                \
+                           row_bytes, queries, nq, out, partial, tiles_per_slice);                                \
         break;
     switch (rc) {
         ANN_RC(1) ANN_RC(2) ANN_RC(3) ANN_RC(4) ANN_RC(5) ANN_RC(6) ANN_RC(7) ANN_RC(8)
