@@ -401,6 +401,22 @@ def main() -> int:
         opt.update({"itopk": opt_itopk, "recall_by_itopk": opt_recalls, "recall_at_k": round(orec, 4), "recall_se": round(orec_se, 4),
                     "qps": round(nq / opt_wall, 1), "ms_per_step": round(opt_wall * 1e3, 3),
                     "per_query": {"rounds": round(ocm[0], 2), "rows_gathered": round(ocm[1], 1), "graph_rows": round(ocm[2], 1)}})
+        opt_sweep = {}
+        for b in w["sweep"]:
+            if b > nq_max or b == nq:
+                continue
+            qb = queries[:b]
+            reps = max(3, min(20, int(2e6 // b)))
+            for _ in range(2):
+                ann.ann_search(h2, qb, k, opt_itopk, width, max_iters, out_ids=out_ids[:b], out_dists=out_d[:b])
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(reps):
+                ann.ann_search(h2, qb, k, opt_itopk, width, max_iters, out_ids=out_ids[:b], out_dists=out_d[:b])
+            torch.cuda.synchronize()
+            opt_sweep[str(b)] = round(b * reps / (time.perf_counter() - t0), 1)
+        opt_sweep[str(nq)] = opt["qps"]
+        opt["qps_by_batch"] = opt_sweep
         gathered = metrics.algorithmic_bytes_per_query(ocm[1], ocm[2], row_bytes, degree, row_bytes, k) * nq
         opt["roofline"] = search_roofline(read_profile("beam_search_kernel", args.workload), "optimized", sha, nq, opt_search_ms,
                                           gathered, None, None, opt_itopk)
