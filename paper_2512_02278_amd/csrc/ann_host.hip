@@ -251,8 +251,8 @@ extern "C" int ann_index_set_option(ann_index_t* h, int option, int64_t value) {
             h->team = (int)value;
             return ANN_OK;
         case ANN_OPT_LANES_PER_ROW: {
-            const RowVariant* v = pick_variant(h->d.dtype, h->d.metric, h->row_bytes, (int)value);
-            if (value < 0 || value > 64 || !v)
+            const RowVariant* v = value < 0 || value > 64 ? nullptr : pick_variant(h->d.dtype, h->d.metric, h->row_bytes, (int)value);
+            if (!v)
                 return fail(ANN_EUNSUPPORTED, "ann_index_set_option: no kernel variant with %lld lanes per row for this index", (long long)value);
             h->variant = v;
             return ANN_OK;
