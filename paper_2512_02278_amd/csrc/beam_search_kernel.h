@@ -240,17 +240,22 @@ struct BeamSearch {
                 id[u] = live ? cid[j] : 0u;
                 row.reload_row(x[u], piece0 + (uint64_t)id[u] * stride, live);
             }
+            // Every lane of a group ends up with the group's key, so lane u of a group takes the key of step u:
+            // one filter, one ballot and one store then serve all U steps (G >= U for every row variant).
+            static_assert(G >= U, "one lane of a group per gather step");
+            uint64_t mine = kInfKey;  // is not below `worst`, whatever that is
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 if (j0 + u * RPS >= m) break;
                 const int j = j0 + u * RPS + grp;
                 const uint32_t okey = row.key(x[u], lane);
                 const uint64_t packed = ((uint64_t)okey << 32) | (uint64_t)(id[u] << 1);  // ids are below 2^31
-                const bool keep = j < m && row.lg == 0 && packed < worst;
-                const uint64_t b = __ballot(keep);
-                if (keep) ckey[rank_below(b, kept)] = packed;
-                kept += __builtin_popcountll(b);
+                mine = (row.lg == u && j < m) ? packed : mine;
             }
+            const bool keep = mine < worst;
+            const uint64_t b = __ballot(keep);
+            if (keep) ckey[rank_below(b, kept)] = mine;
+            kept += __builtin_popcountll(b);
         }
         n_dist += m;
         return kept;
@@ -397,11 +402,30 @@ struct BeamSearch {
         if constexpr (BR == 2) {
             for (; m - base > 64; base += 128) merge_batch<2, 128>(base, m);
         }
-        if (m - base > 16) {
+        if (m - base > 32) {
             for (; base < m; base += 64) merge_batch<1, 64>(base, m);
+        } else if (m - base > 16) {
+            merge_batch<1, 32>(base, m);
         } else if (m - base > 0) {
             merge_batch<1, 16>(base, m);
         }
+        if (m > 0) worst = list_worst();
+    }
+
+    // The first list of a query: the list is still empty, so the sorted keys of the entries are the list
+    // (register 0 of the striped layout is the blocked layout of 64 keys); no merge network.
+    __device__ __forceinline__ void first_list(int m) {
+        if (m > 64) {
+            merge_all(m);
+            return;
+        }
+        int lane = this->lane;
+        asm volatile("" : "+v"(lane));  // see merge_batch
+        uint64_t c[1] = {lane < m ? ckey[lane] : kInfKey};
+        if (m > 32) bitonic_sort_runs<1, 64>(c, lane);
+        else bitonic_sort_runs<1, 32>(c, lane);
+        L[0] = lane < p.itopk ? c[0] : kInfKey;
+        lds_sync();
         if (m > 0) worst = list_worst();
     }
 
@@ -534,7 +558,7 @@ struct BeamSearch {
         lds_sync();
         m = score(m);
         lds_sync();
-        merge_all(m);
+        first_list(m);
         int iters = 0;
         for (; iters < p.max_iters; ++iters) {
             m = expand();

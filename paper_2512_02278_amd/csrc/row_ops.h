@@ -110,8 +110,10 @@ struct RowOps {
                 }
             }
             if constexpr (METRIC == kL2) {
-                // sum (q-x)^2 = qq + xx - 2 qx, exact in int32
-                int32_t part = (int32_t)xx - 2 * (int32_t)qx;
+                // sum (q-x)^2 = qq + xx - 2 qx, exact in int32; a lane's q.x is below 2^23 (at most 48 bytes of
+                // 255 * 255 each), so the 24-bit multiply-add does it in one instruction
+                static_assert(NCH <= 8, "a lane's share of q.x must fit 24 bits");
+                int32_t part = (int32_t)xx + __mul24((int)qx, -2);
                 return (uint32_t)(qq + group_sum<G>(part, lane));
             } else {
                 int32_t s = group_sum<G>((int32_t)qx, lane);
