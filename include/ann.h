@@ -50,7 +50,8 @@ enum {
 typedef struct {
     const void* vectors;      /* DEVICE. n rows, row i at byte offset i*row_stride_bytes, 16-byte aligned */
     int64_t n;                /* number of vectors, 1 .. 2^31-1 */
-    int32_t dim;              /* elements per vector; dim*sizeof(element) must be a multiple of 16 */
+    int32_t dim;              /* elements per vector, at most 1536 (the d of the cost example in Sec. 3.2);
+                                 dim*sizeof(element) must be a multiple of 16 */
     int32_t dtype;            /* ANN_U8 / ANN_F16 / ANN_F32 */
     int64_t row_stride_bytes; /* >= dim*sizeof(element), multiple of 16, below 2^31 (128 keeps rows on cache lines) */
     const int32_t* graph;     /* DEVICE. n*degree ids, row-major; a slot outside [0,n) is empty */

@@ -617,10 +617,10 @@ struct BeamSearch {
 
 // Workgroup b runs on XCD b % 8 (round-robin dispatch), so consecutive queries are
 // kept on one XCD and its L2: query = (b % 8) * q_per_xcd + b / 8.
-// The small uint8 variants are asked to fit 7 wavefronts per SIMD (72 vector registers; 8 would need spills):
+// The small uint8 variants (rows of at most 256 bytes) are asked to fit 7 wavefronts per SIMD (72 vector registers; 8 would need spills):
 // with about 5.5 KB of LDS per query that is also what a compute unit's LDS holds, 28 queries in flight.
 template <class Row, int LPL, int CPL, int TEAM>
-__global__ void __launch_bounds__(64 * TEAM, (TEAM == 1 && Row::kDtype == kU8 && LPL <= 4 && CPL <= 2) ? 7 : 1)
+__global__ void __launch_bounds__(64 * TEAM, (TEAM == 1 && Row::kDtype == kU8 && Row::G * Row::NCH <= 16 && LPL <= 4 && CPL <= 2) ? 7 : 1)
     beam_search_kernel(const SearchParams p) {
     extern __shared__ uint32_t lds[];
     const int64_t b = blockIdx.x;

@@ -1,0 +1,5 @@
+// Kernels of one row variant (see variants.h).
+#include "variants.h"
+namespace ann {
+ANN_DEFINE_ROW_VARIANT(kF16, kL2, 32, 6)
+}

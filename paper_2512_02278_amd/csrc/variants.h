@@ -17,7 +17,8 @@ namespace ann {
 #define ANN_ROW_VARIANTS(X)                                                  \
     X(kU8, kL2, 8, 1) X(kU8, kIP, 8, 1) X(kU8, kL2, 8, 2) X(kU8, kIP, 8, 2) X(kU8, kL2, 4, 2) X(kU8, kIP, 4, 2) \
     X(kF16, kL2, 8, 2) X(kF16, kIP, 8, 2) X(kF16, kL2, 32, 3) X(kF16, kIP, 32, 3) \
-    X(kF32, kL2, 8, 3) X(kF32, kIP, 8, 3) X(kF32, kL2, 32, 4) X(kF32, kIP, 32, 4)
+    X(kF32, kL2, 8, 3) X(kF32, kIP, 8, 3) X(kF32, kL2, 32, 4) X(kF32, kIP, 32, 4)                               \
+    X(kU8, kL2, 32, 3) X(kU8, kIP, 32, 3) X(kF16, kL2, 32, 6) X(kF16, kIP, 32, 6) X(kF32, kL2, 32, 12) X(kF32, kIP, 32, 12)
 
 // List variants (LPL, CPL); a request is served by the first one that is large enough.
 constexpr int kListVariants[][2] = {{1, 1}, {2, 2}, {3, 2}, {4, 2}, {4, 4}, {4, 8}, {8, 8}};

@@ -67,7 +67,8 @@ int main(void) {
     CHECK(ann_index_set_option(h, ANN_OPT_VISITED_WINDOW_BITS, 1 << 17) == ANN_OK);
     CHECK(ann_index_set_option(h, ANN_OPT_VISITED_WINDOW_BITS, (1 << 17) + 1) == ANN_EINVAL);
     CHECK(ann_index_set_option(h, ANN_OPT_LANES_PER_ROW, 8) == ANN_OK);
-    CHECK(ann_index_set_option(h, ANN_OPT_LANES_PER_ROW, 32) == ANN_EUNSUPPORTED);
+    CHECK(ann_index_set_option(h, ANN_OPT_LANES_PER_ROW, 32) == ANN_OK);
+    CHECK(ann_index_set_option(h, ANN_OPT_LANES_PER_ROW, 16) == ANN_EUNSUPPORTED);
     CHECK(strlen(ann_last_error()) > 0);
     CHECK(ann_free(h) == ANN_OK);
     CHECK(ann_free(NULL) == ANN_OK);
@@ -102,8 +103,8 @@ int main(void) {
     d.row_stride_bytes = (int64_t)1 << 31;
     CHECK(ann_index_load(&d, &h) == ANN_EINVAL);
     d = base_desc();
-    d.dim = 512;
-    d.row_stride_bytes = 512;
+    d.dim = 1552;
+    d.row_stride_bytes = 1552;
     CHECK(ann_index_load(&d, &h) == ANN_EUNSUPPORTED);
 
     /* entry points without a handle */

@@ -128,7 +128,7 @@ def test_product_sources_read_no_environment_variables():
     (dict(entry_mode=1), ann.ANN_EINVAL),                       # routed without centroids
     (dict(entry_mode=1, centroids=FAKE, cluster_offsets=FAKE, n_clusters=4, route_c=5), ann.ANN_EINVAL),
     (dict(entry_mode=1, centroids=FAKE, cluster_offsets=FAKE, n_clusters=40, route_c=9), ann.ANN_EINVAL),
-    (dict(dim=512, row_stride_bytes=512), ann.ANN_EUNSUPPORTED),  # uint8 rows above 256 bytes: no variant built
+    (dict(dim=1552, row_stride_bytes=1552), ann.ANN_EUNSUPPORTED),  # rows above 1536 elements: no variant built
 ])
 def test_load_rejects(kw, code):
     rc, h = load(desc(**kw))

@@ -72,12 +72,12 @@ def compare_float(oracle, x, q, metric, gi, gd, oi, od, tol):
     real = gi >= 0
     gk = oracle.keys(x, q, gi, metric)
     scale = np.maximum(np.abs(gk), 1e-30)
-    assert (np.abs(gd.astype(np.float64) - gk)[real] <= tol * scale[real]).all()
+    assert (np.abs(gd.astype(np.float64)[real] - gk[real]) <= tol * scale[real]).all()
     assert np.isinf(gd[~real]).all()
     gs = np.sort(np.where(real, gk, np.inf), axis=1)
     os_ = np.where(oi >= 0, od.astype(np.float64), np.inf)
     both = np.isfinite(gs) & np.isfinite(os_)
-    assert (np.abs(gs - os_)[both] <= tol * np.maximum(np.abs(os_[both]), 1e-30)).all()
+    assert (np.abs(gs[both] - os_[both]) <= tol * np.maximum(np.abs(os_[both]), 1e-30)).all()
     srt = np.sort(gi, axis=1)
     assert not ((srt[:, 1:] == srt[:, :-1]) & (srt[:, 1:] >= 0)).any()
     return float((gi == oi).all(1).mean())
@@ -225,7 +225,7 @@ def test_uint8_heavy_ties_and_inner_product(oracle, torch_cuda):
         check_exact(oracle, torch_cuda, x, g, q, 20, 96, 3, 60, metric=metric, n_entry=16, seed=9)
 
 
-@pytest.mark.parametrize("dim", [16, 48, 128, 160, 256])
+@pytest.mark.parametrize("dim", [16, 48, 128, 160, 256, 272, 768, 1536])
 def test_uint8_dims_and_padded_rows(oracle, torch_cuda, dim):
     rng = np.random.default_rng(dim)
     buf = rng.integers(0, 256, (3000, dim + 32), dtype=np.uint8)
@@ -338,6 +338,55 @@ def test_edge_cases(oracle, torch_cuda, team):
     check_exact(oracle, torch_cuda, x, g, q, 40, 64, 3, 200, n_entry=4, seed=2, options=opts)  # itopk above n
 
 
+def drawn_configuration(seed):
+    """A valid configuration drawn from the whole range the library accepts: list sizes 1..512, up to 512
+    neighbours per round, 1..512 entries, rows of 16..1536 bytes, both metrics and entry rules, teams,
+    visited bitmaps from none to whole clusters, small and large hashes."""
+    rng = np.random.default_rng(1000 + seed)
+    c = {}
+    c["n"] = int(rng.integers(300, 5000))
+    c["dim"] = int(rng.choice([16, 32, 48, 64, 96, 128, 160, 192, 256, 384, 960, 1536]))
+    c["pad"] = int(rng.choice([0, 16, 32]))
+    c["degree"] = int(rng.choice([1, 3, 8, 16, 24, 32, 40, 64]))
+    c["width"] = int(rng.integers(1, min(8, 512 // c["degree"]) + 1))
+    c["itopk"] = int(rng.choice([1, 2, 17, 63, 64, 65, 128, 129, 184, 192, 193, 255, 256, 257, 400, 512]))
+    c["k"] = int(rng.integers(1, c["itopk"] + 1))
+    c["n_entry"] = int(rng.choice([1, 5, 32, 64, 65, 200, 512]))
+    c["metric"] = int(rng.integers(0, 2))
+    c["entry_mode"] = int(rng.integers(0, 2))
+    c["n_centres"] = int(rng.choice([1, 3, 12, 40]))
+    c["route_c"] = int(rng.integers(1, min(8, c["n_centres"]) + 1))
+    c["team"] = int(rng.choice([0, 1, 2, 4]))
+    c["window_bits"] = int(rng.choice([0, 96, 512, 8192, 131072]))
+    c["hash_bias"] = int(rng.choice([-1, 0, 1]))
+    c["max_iters"] = int(rng.choice([0, 1, 7, 60, 200]))
+    c["nq"] = int(rng.integers(1, 130))
+    return rng, c
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_drawn_uint8_configurations_are_bit_exact(oracle, torch_cuda, seed):
+    from paper_2512_02278_amd import ann
+
+    rng, c = drawn_configuration(seed)
+    print(c, flush=True)
+    n, dim = c["n"], c["dim"]
+    x, cen, off = clustered(rng, n, dim + c["pad"], "u8", n_centres=c["n_centres"], spread=25.0)
+    x, cen = x[:, :dim], np.ascontiguousarray(cen[:, :dim])                 # row stride dim + pad bytes
+    g = rng.integers(0, n, (n, c["degree"]), dtype=np.int32)                # half random edges, half near ones
+    near = np.clip(np.arange(n)[:, None] + rng.integers(-20, 21, g.shape), 0, n - 1).astype(np.int32)
+    g = np.where(rng.random(g.shape) < 0.5, g, near)
+    g[rng.random(g.shape) < 0.05] = -1
+    g[rng.random(g.shape) < 0.02] = n + 3
+    q = queries_near(rng, x, c["nq"], "u8")
+    kw = dict(metric=c["metric"], n_entry=c["n_entry"], seed=seed, entry_mode=c["entry_mode"])
+    opts = {ann.ANN_OPT_WAVEFRONTS_PER_QUERY: c["team"], ann.ANN_OPT_VISITED_HASH_BITS_BIAS: c["hash_bias"]}
+    if c["entry_mode"] == 1:
+        kw.update(centroids=cen, offsets=off, route_c=c["route_c"])
+        opts[ann.ANN_OPT_VISITED_WINDOW_BITS] = c["window_bits"]
+    check_exact(oracle, torch_cuda, x, g, q, c["k"], c["itopk"], c["width"], c["max_iters"], options=opts, **kw)
+
+
 # ----------------------------------------------------------------------------- float data
 MIN_IDENTICAL = {"f32": 0.99, "f16": 0.95}  # share of queries whose id lists equal the oracle's (the rest fork at near-ties)
 
@@ -349,6 +398,10 @@ MIN_IDENTICAL = {"f32": 0.99, "f16": 0.95}  # share of queries whose id lists eq
     ("f16", 768, 1, 256, 8, 64, 100),  # text-like shape
     ("f16", 768, 0, 128, 4, 32, 10),
     ("f16", 64, 0, 64, 1, 16, 10),
+    ("f16", 1536, 1, 64, 6, 32, 10),   # the row of the paper's stage-3 example (Sec. 3.2): 3072 bytes
+    ("f16", 1000, 0, 64, 2, 32, 10),   # 2000 bytes: the last piece of the 32-lane, 6-piece variant is partly empty
+    ("f32", 1536, 0, 64, 2, 32, 10),   # 6144 bytes
+    ("f32", 1536, 1, 128, 4, 32, 10),
 ])
 @pytest.mark.parametrize("team", [1, 4])
 def test_float_parity(oracle, torch_cuda, dt, dim, metric, itopk, width, degree, k, team):
@@ -415,6 +468,26 @@ def test_float_parity_routed_entries_windows_and_grouped_order(oracle, torch_cud
     assert identical >= MIN_IDENTICAL[dt], identical
 
 
+@pytest.mark.parametrize("seed", range(12))
+def test_drawn_float_configurations_keep_the_key_rule(oracle, torch_cuda, seed):
+    """Float rows of 16..6144 bytes with drawn list sizes, widths, degrees, entry counts and teams, uniform
+    entries (the routed float path has its own tests above): every key within the tolerance, rank by rank."""
+    from paper_2512_02278_amd import ann
+
+    rng, c = drawn_configuration(100 + seed)
+    dt = "f32" if seed % 2 == 0 else "f16"
+    dim = int(rng.choice([4, 8, 24, 96, 100, 256, 768, 1536] if dt == "f32" else [8, 16, 72, 128, 768, 1536]))
+    print(dt, dim, c, flush=True)
+    x, _, _ = clustered(rng, min(c["n"], 2500), dim, dt)
+    if c["metric"] == 1:
+        x = (x.astype(np.float64) / np.linalg.norm(x.astype(np.float64), axis=1, keepdims=True)).astype(NP_DT[dt])
+    g = rng.integers(0, len(x), (len(x), c["degree"]), dtype=np.int32)
+    g[rng.random(g.shape) < 0.05] = -1
+    q = queries_near(rng, x, min(c["nq"], 60), dt)
+    check_float(oracle, torch_cuda, x, g, q, c["k"], c["itopk"], c["width"], min(c["max_iters"], 60), TOL[dt], 0.9,
+                metric=c["metric"], n_entry=c["n_entry"], seed=seed, options={ann.ANN_OPT_WAVEFRONTS_PER_QUERY: c["team"]})
+
+
 @pytest.mark.parametrize("dt,dim,metric", [("f32", 96, 0), ("f16", 256, 1)])
 def test_a_routing_fork_at_a_near_tie_keeps_the_key_rule_end_to_end(oracle, torch_cuda, dt, dim, metric):
     """Queries placed half way between two centroids: the two keys differ by rounding only, so fp32
@@ -442,7 +515,7 @@ def test_a_routing_fork_at_a_near_tie_keeps_the_key_rule_end_to_end(oracle, torc
 @pytest.mark.parametrize("metric", [0, 1])
 @pytest.mark.parametrize("n_clusters,route_c,nq,dim", [(300, 4, 100, 128), (32, 1, 1, 128), (1000, 8, 777, 128),
                                                         (5, 5, 64, 128), (4097, 3, 300, 128), (333, 2, 130, 64),
-                                                        (200, 8, 65, 256), (70, 1, 40, 32),
+                                                        (200, 8, 65, 256), (70, 1, 40, 32), (130, 3, 50, 1536), (90, 2, 33, 400),
                                                         (16640, 2, 300, 128), (16384, 1, 1000, 128), (2049, 3, 5, 128)])
 def test_uint8_matrix_core_routing_is_exact(oracle, torch_cuda, metric, n_clusters, route_c, nq, dim):
     """uint8 d=128 routing runs on the matrix cores (shifted to int8, exact int32 sums) and must give
@@ -481,7 +554,8 @@ def test_route_matches_oracle(oracle, torch_cuda, metric, no_mfma):
 
     torch = torch_cuda
     rng = np.random.default_rng(3)
-    for dt, dim, nq in (("u8", 128, 100), ("f32", 96, 333), ("f16", 768, 100), ("f32", 8, 70), ("f16", 16, 129)):
+    for dt, dim, nq in (("u8", 128, 100), ("f32", 96, 333), ("f16", 768, 100), ("f32", 8, 70), ("f16", 16, 129),
+                        ("f16", 1536, 90), ("f32", 1536, 65), ("u8", 1536, 77)):
         x, cen, off = clustered(rng, 2000, dim, dt, n_centres=300)
         q = queries_near(rng, x, nq, dt)
         want = oracle.route(cen, q, 4, metric)
@@ -531,7 +605,7 @@ def test_one_million_config_sampled_against_oracle(oracle, torch_cuda):
 
 
 # ----------------------------------------------------------------------------- stage 4, local half
-@pytest.mark.parametrize("dt,dim", [("u8", 128), ("f32", 96), ("f16", 768), ("u8", 16)])
+@pytest.mark.parametrize("dt,dim", [("u8", 128), ("f32", 96), ("f16", 768), ("u8", 16), ("f16", 1536), ("f32", 1536)])
 def test_gather_vectors_matches_oracle(oracle, torch_cuda, dt, dim):
     from paper_2512_02278_amd import ann
 
