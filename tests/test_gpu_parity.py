@@ -287,6 +287,21 @@ def test_cluster_grouped_execution_order(oracle, torch_cuda):
     assert all(np.array_equal(a, b) for a, b in zip(grouped, plain))
 
 
+@pytest.mark.parametrize("entry_mode", [0, 1])
+def test_a_call_longer_than_one_launch(oracle, torch_cuda, entry_mode):
+    """A call of more than 2^22 queries is cut into several launches (of the search, and of the plain routing
+    kernel); a query keeps its position in the call - and with it its entries and, in routed mode, its place in
+    the cluster-grouped order that spans the whole call."""
+    rng = np.random.default_rng(93)
+    x, cen, off = clustered(rng, 3000, 16, "u8", n_centres=20)
+    g = rng.integers(0, 3000, (3000, 4), dtype=np.int32)
+    q = rng.integers(0, 256, ((1 << 22) + 777, 16), dtype=np.uint8)
+    kw = dict(n_entry=2, seed=5, entry_mode=entry_mode)
+    if entry_mode == 1:
+        kw.update(centroids=cen, offsets=off, route_c=2)
+    check_exact(oracle, torch_cuda, x, g, q, 2, 8, 1, 2, **kw)
+
+
 def test_route_ids_outside_the_clusters_are_ignored(oracle, torch_cuda):
     """ann_search_routed takes the routes from the caller.  A route id outside [0, n_clusters) names no
     cluster: the query gets no entries from it (padding if all its routes are such), nothing is read
