@@ -123,9 +123,9 @@ int ann_index_set_option(ann_index_t* handle, int option, int64_t value);
  *   out_dists  DEVICE, nq*k keys: int32 for ANN_U8 (pad INT32_MAX), float otherwise (pad +inf)
  *   stream     hipStream_t, NULL for the default stream
  * Results are valid once the stream has been synchronised.  nq == 0 succeeds and
- * launches nothing.  In routed mode stream-ordered scratch (nq*route_c int32 for the
- * routes; for batches of 16384 queries or more also nq + n_clusters int32 for the
- * cluster-grouped execution order) is allocated and released on `stream`.  On an
+ * launches nothing.  In routed mode one block of stream-ordered scratch (nq*route_c int32 for the
+ * routes, the routing's own temporaries, and for batches of 16384 queries or more nq + n_clusters
+ * int32 for the cluster-grouped execution order) is allocated and released on `stream`.  On an
  * argument error nothing is launched and the outputs are untouched.  Calls on
  * different streams may share a handle.  A route id outside [0, n_clusters) (only possible
  * through ann_search_routed) names no cluster: it gives no entries, and a query whose routes

@@ -1,4 +1,4 @@
-// Beam search kernel: one wavefront (64 lanes) per query.
+// Beam search kernel: one wavefront (64 lanes) per query, or a team of two or four (see BeamSearch).
 //
 // State of a query:
 //   * candidate list: 64*LPL packed keys in registers, ascending, striped layout
@@ -90,7 +90,7 @@ struct BeamSearch {
     static constexpr int G = Row::G;
     static constexpr int NCH = Row::NCH;
     static constexpr int RPS = 64 / G;                                // rows per gather step
-    static constexpr int U = NCH >= 4 ? 1 : (NCH >= 2 ? 3 : 4);       // gather steps in flight
+    static constexpr int U = NCH >= 8 ? 1 : (NCH >= 4 ? 2 : (NCH >= 2 ? 3 : 4));  // gather steps in flight
     static constexpr int BR = LPL >= 2 ? 2 : 1;                       // registers of a sort batch
     static constexpr int kInsertMax = 8;                // at most this many new keys are inserted one by one
 

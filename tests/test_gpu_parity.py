@@ -703,6 +703,52 @@ def test_route_and_search_of_consecutive_batches_on_two_streams(oracle, torch_cu
     ann.ann_free(h)
 
 
+def test_calls_in_flight_on_several_streams_and_host_threads_share_a_handle(torch_cuda):
+    """Calls on different streams, from different host threads, may share a handle: every call takes its scratch
+    as one stream-ordered allocation on its own stream.  Batches of many sizes (below and above the size from which
+    a batch runs grouped by cluster) from four host threads on four streams, nothing synchronised in between, must
+    give what each batch gives alone."""
+    import threading
+
+    from paper_2512_02278_amd import ann, inputs
+
+    torch = torch_cuda
+    dev = "cuda:0"
+    part = inputs.sift_like(60_000, 64, device=dev)
+    inputs.knn_graph_clustered(part, 32)
+    h = ann.ann_index_load(part.vectors, part.graph, n_entry=32, entry_mode=1, seed=5, centroids=part.centres,
+                           cluster_offsets=part.offsets, route_c=2)
+    sizes = [40, 700, 3, 9000, 17_000, 260, 33_000, 1500, 70_000, 5, 20_000, 140_000, 64, 4000]
+    qs = [inputs.sift_like_queries(part, b, seed=300 + i) for i, b in enumerate(sizes)]
+    want = [ann.ann_search(h, q, 10, 64, 2, 40) for q in qs]
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream() for _ in range(4)]
+    got = [[None] * len(sizes) for _ in streams]
+    errors = []
+
+    def worker(t):
+        try:
+            torch.cuda.set_device(0)
+            for rep in range(3):
+                for i in range(len(sizes)):
+                    j = (i * 5 + t * 3 + rep) % len(sizes)    # every thread walks the sizes in its own order
+                    got[t][j] = ann.ann_search(h, qs[j], 10, 64, 2, 40, stream=streams[t])
+        except Exception as e:  # noqa: BLE001 - reported by the main thread
+            errors.append(e)
+
+    threads = [threading.Thread(target=worker, args=(t,)) for t in range(4)]
+    for th in threads:
+        th.start()
+    for th in threads:
+        th.join()
+    torch.cuda.synchronize()
+    assert not errors, errors
+    for t in range(4):
+        for j in range(len(sizes)):
+            assert torch.equal(got[t][j][0], want[j][0]) and torch.equal(got[t][j][1], want[j][1]), (t, j)
+    ann.ann_free(h)
+
+
 def test_calibration_gather_reads_exactly_the_rows(torch_cuda):
     """The measurement aid xors every 32-bit word of the rows it is given; ids outside the table are skipped."""
     from paper_2512_02278_amd import ann
