@@ -10,7 +10,7 @@ index").  Prints ONE JSON line; progress goes to stderr.
 The line carries: queries/s at the smallest itopk whose recall@k, less two standard errors,
 reaches 0.95 on 10 000 exactly solved queries; bytes per query (algorithmic, from the oracle's
 counters; gathered, from the kernel's); the roofline of the beam-search kernel; a batch-size
-sweep; and the CPU oracle timed on this machine's host cores on a sample of the same batch, which
+sweep, alone and with four batches in flight on four streams; and the CPU oracle timed on this machine's host cores on a sample of the same batch, which
 is also checked bit for bit against the GPU's answers.
 
 Roofline.  The timed step runs the batch grouped by cluster, so most gathers hit L2 and the
@@ -27,6 +27,9 @@ HBM figure.
 "value" is measured on the workload's own graph (the cluster-restricted kNN graph).  Where
 the workload names a longer kNN list to start from, "optimized_graph" adds the same
 measurement on the graph that ann_graph_optimize builds from it at the same degree.
+
+--workload embed1536 is the shape of the paper's own cost example for this stage (Sec. 3.2); for it alone
+"vs_baseline" relates the measured rate to the paper's analytic estimate for an A100 ("paper_model").
 
 --profile runs only what the counters are for (a few searches in each configuration, the graph
 construction, a copy of known size) with fixed --itopk / --opt-itopk and prints which launch is
