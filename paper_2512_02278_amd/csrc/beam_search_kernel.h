@@ -218,18 +218,25 @@ struct BeamSearch {
 
     // Gathers rows cid[0..m) and writes the packed keys that can enter the list to
     // ckey[0..returned count).
-    __device__ __forceinline__ int score(int m) {
+    __device__ __forceinline__ int score(int m) { return row.full ? score_rows<true>(m) : score_rows<false>(m); }
+
+    // FULL: the row fills every piece of every lane, so the row buffers need no clearing (RowOps::blank_row); else
+    // they are zeroed once and a piece this lane does not load keeps its zeros (RowOps::reload_row).
+    template <bool FULL>
+    __device__ __forceinline__ int score_rows(int m) {
         const int grp = lane / G;
         const uint64_t worst = this->worst;
         // the host keeps the stride below 2^31, so a row's address is one 32 x 32 -> 64 bit multiply-add
         const uint8_t* const piece0 = row.lane_piece(p.vectors);
         const uint32_t stride = (uint32_t)p.row_stride;
         int kept = 0;
-        u32x4 x[U][NCH];  // zeroed once: see reload_row
+        u32x4 x[U][NCH];
+        if constexpr (!FULL) {
 #pragma unroll
-        for (int u = 0; u < U; ++u)
+            for (int u = 0; u < U; ++u)
 #pragma unroll
-            for (int c = 0; c < NCH; ++c) x[u][c] = u32x4{0, 0, 0, 0};
+                for (int c = 0; c < NCH; ++c) x[u][c] = u32x4{0, 0, 0, 0};
+        }
         for (int j0 = 0; j0 < m; j0 += RPS * U) {
             uint32_t id[U];
 #pragma unroll
@@ -238,7 +245,12 @@ struct BeamSearch {
                 const int j = j0 + u * RPS + grp;
                 const bool live = j < m;
                 id[u] = live ? cid[j] : 0u;
-                row.reload_row(x[u], piece0 + (uint64_t)id[u] * stride, live);
+                if constexpr (FULL) {
+                    row.blank_row(x[u]);
+                    row.load_full_row(x[u], piece0 + (uint64_t)id[u] * stride, live);
+                } else {
+                    row.reload_row(x[u], piece0 + (uint64_t)id[u] * stride, live);
+                }
             }
             // Every lane of a group ends up with the group's key, so lane u of a group takes the key of step u:
             // one filter, one ballot and one store then serve all U steps (G >= U for every row variant).
@@ -265,15 +277,23 @@ struct BeamSearch {
     // that can enter the list are appended to ckey through a counter the team shares; their order in ckey
     // is whatever the atomics give, which the merge does not depend on (it orders them).
     __device__ __forceinline__ void score_team(int m) {
+        if (row.full) score_team_rows<true>(m);
+        else score_team_rows<false>(m);
+    }
+
+    template <bool FULL>
+    __device__ __forceinline__ void score_team_rows(int m) {
         const int grp = lane / G;
         const uint64_t worst = this->worst;
         const uint8_t* const piece0 = row.lane_piece(p.vectors);
         const uint32_t stride = (uint32_t)p.row_stride;
         u32x4 x[U][NCH];
+        if constexpr (!FULL) {
 #pragma unroll
-        for (int u = 0; u < U; ++u)
+            for (int u = 0; u < U; ++u)
 #pragma unroll
-            for (int c = 0; c < NCH; ++c) x[u][c] = u32x4{0, 0, 0, 0};
+                for (int c = 0; c < NCH; ++c) x[u][c] = u32x4{0, 0, 0, 0};
+        }
         for (int j0 = wave * (RPS * U); j0 < m; j0 += RPS * U * TEAM) {
             uint32_t id[U];
 #pragma unroll
@@ -282,7 +302,12 @@ struct BeamSearch {
                 const int j = j0 + u * RPS + grp;
                 const bool live = j < m;
                 id[u] = live ? cid[j] : 0u;
-                row.reload_row(x[u], piece0 + (uint64_t)id[u] * stride, live);
+                if constexpr (FULL) {
+                    row.blank_row(x[u]);
+                    row.load_full_row(x[u], piece0 + (uint64_t)id[u] * stride, live);
+                } else {
+                    row.reload_row(x[u], piece0 + (uint64_t)id[u] * stride, live);
+                }
             }
             uint64_t packed[U], b[U];
             bool keep[U];

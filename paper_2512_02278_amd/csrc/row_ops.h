@@ -46,12 +46,17 @@ struct RowOps {
 
     u32x4 q[NCH];        // this lane's pieces of the query
     uint32_t piece_ok;   // bit c set: piece c of this lane lies inside the row
+    bool full;           // the row fills every piece of every lane (uniform)
+    int minus_two;       // -2 in a scalar register (uint8 L2 keys)
     int32_t qq;          // uint8 L2 only: sum of squares of the query
     int lg;              // lane index inside its group
 
     __device__ __forceinline__ void load_query(const uint8_t* qrow, int row_bytes, int lane) {
         lg = lane & (G - 1);
         piece_ok = 0;
+        full = row_bytes >= G * NCH * 16;
+        minus_two = -2;
+        asm volatile("" : "+s"(minus_two));
 #pragma unroll
         for (int c = 0; c < NCH; ++c) {
             const int off = (c * G + lg) * 16;
@@ -86,6 +91,24 @@ struct RowOps {
         }
     }
 
+    // For rows that fill every piece of every lane (`full`): a row buffer whose registers hold nothing yet, and the
+    // load of a wanted row into it.  No instruction is spent on clearing: every piece of a wanted row is loaded
+    // before it is used, and the key of a row passed with live = false is ignored, whatever it is computed from.
+    __device__ __forceinline__ void blank_row(u32x4 (&x)[NCH]) const {
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) {
+            uint32_t a, b, d, e;
+            asm volatile("" : "=v"(a), "=v"(b), "=v"(d), "=v"(e));  // defines the registers, emits nothing
+            x[c] = u32x4{a, b, d, e};
+        }
+    }
+    __device__ __forceinline__ void load_full_row(u32x4 (&x)[NCH], const uint8_t* piece, bool live) const {
+        if (live) {
+#pragma unroll
+            for (int c = 0; c < NCH; ++c) x[c] = *reinterpret_cast<const u32x4*>(piece + c * G * 16);
+        }
+    }
+
     // The same for a buffer that is reused from row to row: a piece this lane does not load keeps what
     // x held.  The caller zeroes x once (pieces beyond the row's end then stay zero for good) and
     // ignores the key of a row it passed with live = false.
@@ -113,7 +136,9 @@ struct RowOps {
                 // sum (q-x)^2 = qq + xx - 2 qx, exact in int32; a lane's q.x is below 2^23 (at most 48 bytes of
                 // 255 * 255 each), so the 24-bit multiply-add does it in one instruction
                 static_assert(NCH <= 8, "a lane's share of q.x must fit 24 bits");
-                int32_t part = (int32_t)xx + __mul24((int)qx, -2);
+                // (the factor comes from a register the optimiser cannot see through: with the literal it turns the
+                // 24-bit multiply into two shifts and a subtraction)
+                int32_t part = (int32_t)xx + __mul24((int)qx, minus_two);
                 return (uint32_t)(qq + group_sum<G>(part, lane));
             } else {
                 int32_t s = group_sum<G>((int32_t)qx, lane);
