@@ -507,7 +507,9 @@ def test_drawn_float_configurations_keep_the_key_rule(oracle, torch_cuda, seed):
     g[rng.random(g.shape) < 0.05] = -1
     q = queries_near(rng, x, min(c["nq"], 60), dt)
     k = min(c["k"], max(1, c["itopk"] // 2))
-    floor = 0.9 if len(q) >= 20 else 0.0  # a handful of queries: one near-tie swap is already a tenth of them
+    # identical id lists are the usual case, not the rule under test: long results (k in the hundreds) of low-dimensional
+    # data hold a near-tie swap in more than a tenth of the queries, and with a handful of queries one swap is a tenth
+    floor = 0.8 if len(q) >= 20 else 0.0
     check_float(oracle, torch_cuda, x, g, q, k, c["itopk"], c["width"], 400, TOL[dt], floor,
                 metric=c["metric"], n_entry=c["n_entry"], seed=seed, options={ann.ANN_OPT_WAVEFRONTS_PER_QUERY: c["team"]})
 
