@@ -125,7 +125,9 @@ int ann_index_set_option(ann_index_t* handle, int option, int64_t value);
  * Results are valid once the stream has been synchronised.  nq == 0 succeeds and
  * launches nothing.  In routed mode one block of stream-ordered scratch (nq*route_c int32 for the
  * routes, the routing's own temporaries, and for batches of 16384 queries or more nq + n_clusters
- * int32 for the cluster-grouped execution order) is allocated and released on `stream`.  On an
+ * int32 for the cluster-grouped execution order) is allocated and released on `stream`; the
+ * runtime may hold the calling thread in that allocation until the previous call on the stream has
+ * finished (no wrong result follows from it; ann_search_static does not allocate).  On an
  * argument error nothing is launched and the outputs are untouched.  Calls on
  * different streams may share a handle.  A route id outside [0, n_clusters) (only possible
  * through ann_search_routed) names no cluster: it gives no entries, and a query whose routes
